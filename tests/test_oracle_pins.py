@@ -1,0 +1,437 @@
+"""Pins for the CPU oracle: each check ties an oracle function to something
+other than itself -- hand-worked fixtures, closed forms, brute force written
+out in scalar Python, library routines for the special cases that reduce to
+them.  No GPU, no HIP library."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import vorta_oracle as vo
+from synth_inputs import CONFIGS, get_config, make_qkv
+from helpers import f64, smooth_field, spec_of
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def read_mask_fixture(name):
+    out, cur = {}, None
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line.startswith("["):
+            cur = line.strip("[]")
+            out[cur] = []
+        else:
+            out[cur].append([c == "1" for c in line])
+    return {k: np.array(v, dtype=bool) for k, v in out.items()}
+
+
+# ----------------------------------------------------------------- Eq. 2 ---
+
+def scalar_attention(Q, K, V, scale, keys_of_row=None):
+    """Softmax attention with nothing but Python floats."""
+    n, d = len(Q), len(V[0])
+    out = [[0.0] * d for _ in range(n)]
+    for i in range(n):
+        keys = range(len(K)) if keys_of_row is None else keys_of_row(i)
+        s = [scale * sum(a * b for a, b in zip(Q[i], K[j])) for j in keys]
+        m = max(s)
+        e = [math.exp(x - m) for x in s]
+        z = sum(e)
+        for w, j in zip(e, keys):
+            for c in range(d):
+                out[i][c] += (w / z) * V[j][c]
+    return np.array(out)
+
+
+def test_full_attention_matches_scalar_python():
+    rng = np.random.default_rng(0)
+    Q, K, V = rng.standard_normal((3, 37, 8))
+    spec = vo.LayerSpec(grid=(1, 1, 37), tile=(1, 1, 37), window=(1, 1, 1))
+    got = vo.full_attention(Q, K, V, spec)
+    want = scalar_attention(Q.tolist(), K.tolist(), V.tolist(), 1 / math.sqrt(8))
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-13)
+
+
+def test_full_attention_matches_library_sdpa():
+    rng = np.random.default_rng(1)
+    Q, K, V = rng.standard_normal((3, 200, 16))
+    spec = vo.LayerSpec(grid=(2, 10, 10), tile=(1, 5, 5), window=(1, 1, 1))
+    got = vo.full_attention(Q, K, V, spec)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q)[None], torch.from_numpy(K)[None], torch.from_numpy(V)[None])[0].numpy()
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+
+
+def test_attention_closed_forms():
+    rng = np.random.default_rng(2)
+    Q, K, V = rng.standard_normal((3, 50, 4))
+    # zero scale: uniform weights -> every row is the mean of V
+    spec0 = vo.LayerSpec(grid=(1, 5, 10), tile=(1, 5, 10), window=(1, 1, 1), scale=0.0)
+    np.testing.assert_allclose(vo.full_attention(Q, K, V, spec0),
+                               np.broadcast_to(V.mean(0), V.shape), atol=1e-14)
+    # two keys: weights are a logistic function of the score difference
+    q = np.array([[1.0, 2.0]]); k = np.array([[0.5, -1.0], [2.0, 0.25]]); v = np.array([[1.0, 0.0], [0.0, 1.0]])
+    s = (q @ k.T)[0] * 0.7
+    w1 = 1 / (1 + math.exp(s[0] - s[1]))
+    np.testing.assert_allclose(vo.attention_rows(q, k, v, 0.7), [[1 - w1, w1]], atol=1e-15)
+    # a key that matches overwhelmingly -> its value row
+    big = vo.attention_rows(np.array([[50.0, 0.0]]), np.array([[1.0, 0], [-1.0, 0]]),
+                            np.array([[3.0], [7.0]]), 1.0)
+    np.testing.assert_allclose(big, [[3.0]], atol=1e-12)
+    # rows of P sum to one
+    P = vo.softmax_rows(rng.standard_normal((9, 33)) * 5)
+    assert np.abs(P.sum(1) - 1).max() < 1e-12 and (P >= 0).all()
+    # permuting keys and values together changes nothing; permuting only V does
+    perm = rng.permutation(50)
+    spec = vo.LayerSpec(grid=(1, 5, 10), tile=(1, 5, 10), window=(1, 1, 1))
+    base = vo.full_attention(Q, K, V, spec)
+    np.testing.assert_allclose(vo.full_attention(Q, K[perm], V[perm], spec), base, atol=1e-13)
+    assert np.abs(vo.full_attention(Q, K, V[perm], spec) - base).max() > 1e-3
+
+
+@pytest.mark.parametrize("route", [0, 1, 2])
+def test_constant_values_give_constant_output(route):
+    rng = np.random.default_rng(3)
+    grid = (4, 6, 6)
+    Q, K = (smooth_field(rng, grid, 8) for _ in range(2))
+    V = np.tile(np.array([[1.5, -2.0, 0.25, 4.0, 0, 1, 2, 3]]), (Q.shape[0], 1))
+    spec = vo.LayerSpec(grid=grid, tile=(2, 2, 2), window=(1, 3, 1))
+    out = vo.head_attention(route, Q, K, V, spec)
+    np.testing.assert_allclose(out, V, atol=1e-13)
+
+
+# ------------------------------------------------------------ Algorithm 1 ---
+
+@pytest.mark.parametrize("name,grid,tile,window", [
+    ("sta_mask_1x1x8_tile2_win3.txt", (1, 1, 8), (1, 1, 2), (1, 1, 3)),
+    ("sta_mask_2x2x4_tile1x1x2_win1.txt", (2, 2, 4), (1, 1, 2), (1, 1, 1)),
+    ("sta_mask_3x1x2_tile1x1x1_win3x1x1.txt", (3, 1, 2), (1, 1, 1), (3, 1, 1)),
+])
+def test_mask_hand_worked_fixtures(name, grid, tile, window):
+    for mode, want in read_mask_fixture(name).items():
+        got = vo.sta_mask_dense(grid, tile, window, mode)
+        assert (got == want).all(), (name, mode)
+        rows = np.stack([vo.sta_mask_row(i, grid, tile, window, mode) for i in range(len(want))])
+        assert (rows == want).all()
+
+
+@pytest.mark.parametrize("window", [(1, 1, 1), (3, 3, 3), (1, 3, 5), (5, 1, 3), (2, 4, 2)])
+def test_mask_row_form_equals_double_loop_and_invariants(window):
+    grid, tile = (4, 6, 6), (2, 2, 3)
+    n = vo.tile_grid(grid, tile)                      # (2, 3, 2)
+    M = vo.sta_mask_dense(grid, tile, window)
+    L = M.shape[0]
+    for i in range(L):
+        assert (vo.sta_mask_row(i, grid, tile, window) == M[i]).all()
+    # block-wise dense (section 3.2): constant over (query tile) x (key tile) blocks
+    tid = np.array([np.ravel_multi_index(vo.get_tile_id_3d(i, grid, tile), n) for i in range(L)])
+    for a in range(n[0] * n[1] * n[2]):
+        for b in range(n[0] * n[1] * n[2]):
+            blk = M[np.ix_(tid == a, tid == b)]
+            assert blk.all() or not blk.any()
+    # clamped windows: every query sees prod(min(2*floor(w/2)+1, n)) tiles
+    per_axis = [min(2 * (w // 2) + 1, nd) for w, nd in zip(window, n)]
+    assert (M.sum(1) == np.prod(per_axis) * np.prod(tile)).all()
+    # a token always sees its own tile
+    assert M[np.arange(L), np.arange(L)].all()
+
+
+def test_mask_covers_everything_when_window_spans_grid():
+    grid, tile = (4, 6, 6), (2, 2, 3)
+    n = vo.tile_grid(grid, tile)
+    for mode in ("clamp", "identity"):
+        w = tuple(2 * nd - 1 for nd in n)
+        assert vo.sta_mask_dense(grid, tile, w, mode).all()
+    # the Tiny benchmark layer: 2x2x2 tiles under a 3x3x3 window is dense
+    tiny = get_config("tiny")
+    assert vo.tile_grid(tiny.grid, tiny.tile) == (2, 2, 2)
+    assert all(vo.sta_mask_row(i, tiny.grid, tiny.tile, tiny.window).all() for i in range(0, 256, 17))
+    # interior tiles: both centre rules agree
+    g, t, w = (1, 1, 14), (1, 1, 2), (1, 1, 3)
+    a, b = vo.sta_mask_dense(g, t, w, "clamp"), vo.sta_mask_dense(g, t, w, "identity")
+    assert (a[2:12] == b[2:12]).all() and not (a[:2] == b[:2]).all()
+
+
+def test_window_route_equals_full_when_mask_is_dense_and_scalar_brute_force_otherwise():
+    rng = np.random.default_rng(4)
+    grid = (2, 4, 4)
+    Q, K, V = (smooth_field(rng, grid, 6) for _ in range(3))
+    dense = vo.LayerSpec(grid=grid, tile=(1, 2, 2), window=(3, 3, 3))
+    assert vo.sta_mask_dense(grid, (1, 2, 2), (3, 3, 3)).all()
+    np.testing.assert_allclose(vo.window_attention(Q, K, V, dense), vo.full_attention(Q, K, V, dense),
+                               atol=1e-12)
+    sparse = vo.LayerSpec(grid=grid, tile=(1, 2, 2), window=(1, 1, 1))
+    M = vo.sta_mask_dense(grid, sparse.tile, sparse.window)
+    want = scalar_attention(Q.tolist(), K.tolist(), V.tolist(), 1 / math.sqrt(6),
+                            keys_of_row=lambda i: [j for j in range(32) if M[i, j]])
+    got = vo.window_attention(Q, K, V, sparse)
+    np.testing.assert_allclose(got, want, atol=1e-13)
+    assert np.abs(got - vo.full_attention(Q, K, V, sparse)).max() > 1e-3
+    # rows argument picks rows of the same result
+    np.testing.assert_allclose(vo.window_attention(Q, K, V, sparse, rows=[5, 31, 0]), want[[5, 31, 0]],
+                               atol=1e-13)
+
+
+def test_window_route_text_tokens():
+    rng = np.random.default_rng(5)
+    grid, n_text = (2, 2, 4), 3
+    L = 16
+    Q, K, V = rng.standard_normal((3, L + n_text, 4))
+    spec = vo.LayerSpec(grid=grid, tile=(1, 1, 2), window=(1, 1, 1), n_text=n_text)
+    M = vo.sta_mask_dense(grid, spec.tile, spec.window)
+    def keys(i):
+        if i >= L:
+            return list(range(L + n_text))
+        return [j for j in range(L) if M[i, j]] + list(range(L, L + n_text))
+    want = scalar_attention(Q.tolist(), K.tolist(), V.tolist(), 0.5, keys_of_row=keys)
+    np.testing.assert_allclose(vo.window_attention(Q, K, V, spec), want, atol=1e-13)
+
+
+# -------------------------------------------------------------------- BCS ---
+
+def test_bcs_fig3_counts_and_centre():
+    for line in open(os.path.join(GOLDEN, "bcs_fig3.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        bf, bh, bw, num, den, centre, k = map(int, line.split())
+        buckets = list(vo.bcs_buckets((bf, bh, bw), (bf, bh, bw)))
+        assert len(buckets) == 1
+        idx, c = buckets[0]
+        assert c == centre and list(idx) == list(range(bf * bh * bw))
+        assert vo.bcs_prune_count(bf * bh * bw, num, den) == k
+
+
+def test_bcs_buckets_partition_the_grid_and_clip_at_border():
+    grid, bucket = (5, 8, 7), (2, 3, 2)
+    seen = np.zeros(5 * 8 * 7, dtype=int)
+    shapes = set()
+    for idx, c in vo.bcs_buckets(grid, bucket):
+        seen[idx] += 1
+        coords = np.array([vo.token_coord(int(i), grid) for i in idx])
+        ext = coords.max(0) - coords.min(0) + 1
+        shapes.add(tuple(ext))
+        assert len(idx) == ext.prod() and (ext <= bucket).all()
+        assert (coords.min(0) % np.array(bucket) == 0).all()             # origin aligned
+        assert tuple(coords[c] - coords.min(0)) == tuple(ext // 2)       # centre = floor(b'/2)
+        assert list(idx) == sorted(idx)                                  # local raster order
+    assert (seen == 1).all()
+    assert (1, 2, 1) in shapes and (2, 3, 2) in shapes
+
+
+@pytest.mark.parametrize("cfg", CONFIGS, ids=lambda c: c.name)
+def test_bcs_half_ratio_halves_every_benchmark_grid(cfg):
+    """Core-set ratio 0.5 (appendix) keeps exactly half the tokens on all five
+    grids, so attention cost falls to a quarter (introduction)."""
+    kept = sum(len(idx) - vo.bcs_prune_count(len(idx), cfg.keep_num, cfg.keep_den)
+               for idx, _ in vo.bcs_buckets(cfg.grid, cfg.bucket))
+    assert 2 * kept == cfg.n_video
+
+
+def test_bcs_similarity_count_is_linear(monkeypatch):
+    """L/(thw) buckets x (thw - 1) similarities (appendix complexity paragraph)."""
+    calls = []
+    real = vo.cosine_to_centre
+    monkeypatch.setattr(vo, "cosine_to_centre", lambda a, b: calls.append(1) or real(a, b))
+    grid = (4, 6, 6)
+    feat = np.random.default_rng(6).standard_normal((144, 5))
+    vo.bcs_select(feat, grid, (2, 3, 2))
+    assert len(calls) == 144 - 144 // 12
+
+
+def test_bcs_prunes_the_near_copies_of_the_centre():
+    rng = np.random.default_rng(7)
+    grid = bucket = (2, 3, 2)
+    feat = rng.standard_normal((12, 16))
+    centre = 9
+    near = [0, 3, 4, 7, 10, 11]
+    for j in near:
+        feat[j] = feat[centre] * rng.uniform(0.5, 2.0) + 0.01 * rng.standard_normal(16)
+    keep_idx, assign, gap = vo.bcs_select(feat, grid, bucket)
+    assert sorted(keep_idx) == sorted(set(range(12)) - set(near))
+    assert list(keep_idx) == sorted(keep_idx)                      # slots in local raster order
+    for j in range(12):
+        want = centre if j in near else j
+        assert keep_idx[assign[j]] == want
+    assert gap > 0.1
+    # scaling a token does not change a cosine; flipping its sign does
+    feat2 = feat.copy(); feat2[near[0]] *= -1
+    k2, _, _ = vo.bcs_select(feat2, grid, bucket)
+    assert near[0] in k2
+
+
+def test_bcs_tie_break_prunes_smaller_index_first():
+    feat = np.ones((12, 4))                                        # all cosines equal
+    keep_idx, assign, gap = vo.bcs_select(feat, (2, 3, 2), (2, 3, 2))
+    assert list(keep_idx) == [6, 7, 8, 9, 10, 11] and gap == 0.0   # 0..5 pruned into centre 9
+    assert list(assign) == [3, 3, 3, 3, 3, 3, 0, 1, 2, 3, 4, 5]
+    z = np.zeros((12, 4)); z[9] = 1                                # zero-norm tokens: cosine 0
+    assert list(vo.bcs_select(z, (2, 3, 2), (2, 3, 2))[0]) == [6, 7, 8, 9, 10, 11]
+
+
+def test_bcs_identity_cases_reduce_core_set_route_to_full_attention():
+    rng = np.random.default_rng(8)
+    grid = (3, 4, 5)
+    Q, K, V = (smooth_field(rng, grid, 8) for _ in range(3))
+    for kw in (dict(keep_num=1, keep_den=1), dict(bucket=(1, 1, 1))):
+        spec = vo.LayerSpec(grid=grid, tile=(1, 1, 1), window=(1, 1, 1), **kw)
+        keep_idx, assign, _ = vo.bcs_select(K, grid, spec.bucket, spec.keep_num, spec.keep_den)
+        # nothing pruned: the core-set is all tokens (bucket-major order; the identity for
+        # one-token buckets) and every token reads its own slot
+        assert sorted(keep_idx) == list(range(60)) and list(keep_idx[assign]) == list(range(60))
+        if spec.bucket == (1, 1, 1):
+            assert list(keep_idx) == list(range(60))
+        np.testing.assert_allclose(vo.coreset_attention(Q, K, V, spec), vo.full_attention(Q, K, V, spec),
+                                   atol=1e-12)
+
+
+def test_bcs_pool_conserves_mass_and_unpool_inverts_on_kept_tokens():
+    rng = np.random.default_rng(9)
+    grid = (5, 6, 7)
+    X = smooth_field(rng, grid, 6)
+    keep_idx, assign, _ = vo.bcs_select(X, grid, (2, 3, 2))
+    Xc = vo.bcs_pool(X, keep_idx, assign)
+    size = np.bincount(assign, minlength=len(keep_idx))
+    np.testing.assert_allclose((size[:, None] * Xc).sum(0), X.sum(0), atol=1e-10)
+    singles = size == 1
+    np.testing.assert_array_equal(Xc[singles], X[keep_idx[singles]])          # kept tokens untouched
+    assert (assign[keep_idx] == np.arange(len(keep_idx))).all()               # a kept token owns its slot
+    np.testing.assert_array_equal(vo.bcs_unpool(Xc, assign)[keep_idx], Xc)
+
+
+@pytest.mark.parametrize("axis,bucket", [(0, (2, 1, 1)), (1, (1, 2, 1)), (2, (1, 1, 2))])
+def test_bcs_with_two_token_buckets_is_average_pooling(axis, bucket):
+    """Bucket of two at ratio 0.5: the one non-centre token is always pruned, so
+    pool() is 2x average pooling along that axis (the ablation's AP variants,
+    section 4.3) and unpool() is nearest-neighbour upsampling."""
+    rng = np.random.default_rng(10)
+    grid = (4, 6, 8)
+    X = rng.standard_normal((4 * 6 * 8, 3))
+    keep_idx, assign, _ = vo.bcs_select(X, grid, bucket)
+    Xc = vo.bcs_pool(X, keep_idx, assign)
+    vol = torch.from_numpy(X.reshape(*grid, 3)).permute(3, 0, 1, 2)[None]
+    pooled = torch.nn.functional.avg_pool3d(vol, kernel_size=bucket)
+    np.testing.assert_allclose(Xc, pooled[0].permute(1, 2, 3, 0).reshape(-1, 3).numpy(), atol=1e-14)
+    up = pooled.repeat_interleave(2, dim=2 + axis)[0].permute(1, 2, 3, 0).reshape(-1, 3).numpy()
+    np.testing.assert_allclose(vo.bcs_unpool(Xc, assign), up, atol=1e-14)
+
+
+def scalar_coreset(Q, K, V, grid, bucket, scale, n_text=0):
+    """Core-set route re-derived with Python scalars only, from section 3.2."""
+    F, H, W = grid
+    L, d = F * H * W, len(Q[0])
+    dot = lambda a, b: sum(x * y for x, y in zip(a, b))
+    groups = []                                     # (members, representative token or None)
+    for f0 in range(0, F, bucket[0]):
+        for h0 in range(0, H, bucket[1]):
+            for w0 in range(0, W, bucket[2]):
+                fs = range(f0, min(f0 + bucket[0], F)); hs = range(h0, min(h0 + bucket[1], H))
+                ws = range(w0, min(w0 + bucket[2], W))
+                toks = [(f * H + h) * W + w for f in fs for h in hs for w in ws]
+                cf, ch, cw = fs[len(fs) // 2], hs[len(hs) // 2], ws[len(ws) // 2]
+                c = (cf * H + ch) * W + cw
+                sims = []
+                for t in toks:
+                    if t != c:
+                        den = math.sqrt(dot(K[c], K[c]) * dot(K[t], K[t]))
+                        sims.append((-(dot(K[c], K[t]) / den if den else 0.0), t))
+                k = min(len(toks) - 1, len(toks) // 2)
+                dropped = [t for _, t in sorted(sims)[:k]]
+                for t in toks:
+                    if t not in dropped:
+                        groups.append([t] + (dropped if t == c else []))
+    groups += [[L + t] for t in range(n_text)]
+    mean = lambda X, g: [sum(X[t][c] for t in g) / len(g) for c in range(d)]
+    Qc, Kc, Vc = ([mean(X, g) for g in groups] for X in (Q, K, V))
+    Oc = scalar_attention(Qc, Kc, Vc, scale)
+    out = np.zeros((L + n_text, d))
+    for s, g in enumerate(groups):
+        out[g] = Oc[s]
+    return out
+
+
+@pytest.mark.parametrize("grid,n_text", [((2, 3, 4), 0), ((3, 4, 3), 2)])
+def test_coreset_route_matches_scalar_rederivation(grid, n_text):
+    rng = np.random.default_rng(11)
+    L = grid[0] * grid[1] * grid[2]
+    Q, K, V = (np.concatenate([smooth_field(rng, grid, 5), rng.standard_normal((n_text, 5))]) for _ in range(3))
+    spec = vo.LayerSpec(grid=grid, tile=(1, 1, 1), window=(1, 1, 1), n_text=n_text, scale=0.4)
+    want = scalar_coreset(Q.tolist(), K.tolist(), V.tolist(), grid, (2, 3, 2), 0.4, n_text)
+    got = vo.coreset_attention(Q, K, V, spec)
+    np.testing.assert_allclose(got, want, atol=1e-13)
+    np.testing.assert_allclose(vo.coreset_attention(Q, K, V, spec, rows=[L + n_text - 1, 3, 0]),
+                               want[[L + n_text - 1, 3, 0]], atol=1e-13)
+    assert np.abs(got - vo.full_attention(Q, K, V, spec)).max() > 1e-3
+
+
+# ---------------------------------------------------------------- routing ---
+
+def test_hard_route_follows_eq4_and_sends_ties_to_full():
+    a = np.array([[0.5, 0.3, 0.2], [0.2, 0.5, 0.3], [0.2, 0.3, 0.5],
+                  [0.4, 0.4, 0.2], [0.2, 0.4, 0.4], [0.4, 0.2, 0.4], [1 / 3, 1 / 3, 1 / 3]])
+    assert list(vo.hard_route(a)) == [0, 1, 2, 0, 0, 0, 0]
+
+
+def test_router_gates_are_a_softmax_of_a_linear_map():
+    rng = np.random.default_rng(12)
+    T, W = rng.standard_normal(7), rng.standard_normal((4, 7, 3))
+    g = vo.router_gates(T, W)
+    assert g.shape == (4, 3) and np.abs(g.sum(1) - 1).max() < 1e-14
+    z = [sum(T[i] * W[2, i, k] for i in range(7)) for k in range(3)]
+    e = [math.exp(x) for x in z]
+    np.testing.assert_allclose(g[2], [x / sum(e) for x in e], atol=1e-14)
+    np.testing.assert_allclose(vo.router_gates(np.zeros(7), W), 1 / 3)
+
+
+def test_layer_dispatches_each_head_by_its_route_and_soft_mixture_blends():
+    rng = np.random.default_rng(13)
+    grid = (2, 6, 4)
+    Q, K, V = (np.stack([smooth_field(rng, grid, 4) for _ in range(3)]) for _ in range(3))
+    spec = vo.LayerSpec(grid=grid, tile=(1, 3, 2), window=(1, 1, 1))
+    out = vo.routed_attention_layer(Q, K, V, [2, 0, 1], spec)
+    np.testing.assert_array_equal(out[0], vo.coreset_attention(Q[0], K[0], V[0], spec))
+    np.testing.assert_array_equal(out[1], vo.full_attention(Q[1], K[1], V[1], spec))
+    np.testing.assert_array_equal(out[2], vo.window_attention(Q[2], K[2], V[2], spec))
+    onehot = np.eye(3)[[2, 0, 1]]
+    np.testing.assert_allclose(vo.soft_mixture_layer(Q, K, V, onehot, spec), out, atol=1e-14)
+    mix = vo.soft_mixture_layer(Q, K, V, np.full((3, 3), 1 / 3), spec)
+    want0 = sum(vo.head_attention(r, Q[0], K[0], V[0], spec) for r in range(3)) / 3
+    np.testing.assert_allclose(mix[0], want0, atol=1e-14)
+
+
+# ------------------------------------------------------- synthetic inputs ---
+
+def test_synthetic_fields_follow_the_recipe():
+    from scipy.ndimage import gaussian_filter1d
+    from synth_inputs import blur_matrix
+    x = np.random.default_rng(14).standard_normal(23)
+    np.testing.assert_allclose(blur_matrix(23).numpy() @ x,
+                               gaussian_filter1d(x, sigma=2.0, truncate=4.0, mode="reflect"), atol=1e-13)
+    np.testing.assert_allclose(blur_matrix(4).numpy() @ x[:4],
+                               gaussian_filter1d(x[:4], sigma=2.0, truncate=4.0, mode="reflect"), atol=1e-13)
+    cfg = get_config("tiny")
+    q, k, v = make_qkv(cfg)
+    q2, _, _ = make_qkv(cfg)
+    assert q.shape == (2, 256, 64) and q.dtype == torch.float32 and torch.equal(q, q2)
+    for t in (q, k, v):
+        assert abs(float(t.mean())) < 0.05 and abs(float(t.std()) - 1) < 0.05
+    assert not torch.equal(q, k)
+    # neighbours along W are correlated, far tokens are not
+    kk = f64(k[0]).reshape(4, 8, 8, 64)
+    near = np.mean(kk[:, :, :-1] * kk[:, :, 1:]); far = np.mean(kk[:, :, 0] * kk[:, :, 7])
+    assert near > 0.5 and abs(far) < 0.35
+    q0, _, _ = make_qkv(cfg, layout=0)
+    assert q0.shape == (256, 2, 64) and torch.equal(q0.transpose(0, 1), q)
+
+
+def test_route_vectors():
+    from synth_inputs import make_routes
+    assert list(make_routes(get_config("single"))) == [0, 0, 1, 1, 1, 2, 2, 2]
+    for name, counts in (("wan480p", (8, 16, 16)), ("wan720p", (6, 18, 16)), ("hunyuan720p", (2, 12, 10))):
+        r = make_routes(get_config(name))
+        assert tuple(int((r == i).sum()) for i in range(3)) == counts
+        assert torch.equal(r, make_routes(get_config(name)))
