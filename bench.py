@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the routed attention layer on one MI355X.
+
+A step is one pass of the whole hot path -- reorder to tiles, core-set index build, pool,
+the fused routed attention launch, scatter back -- over one seeded synthetic layer, with
+Q/K/V already resident in HBM.  Prints ONE JSON line.
+
+  value       effective TFLOP/s of the whole layer call: FLOPs of the two contractions
+              actually required by each head's route (padding and softmax not counted)
+              / wall time per step
+  roofline    the fused attention kernel alone, timed with events on its stream in a second
+              pass over the same buffers, against the dense bf16 MFMA peak
+  cpu_baseline the fp64 NumPy oracle on a bounded sample of the same layer's rows,
+              extrapolated to one layer (context, not a target)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "ms per routed attention layer + effective TFLOP/s (% MFMA peak) at 75.6k tokens"
+MFMA_PEAK_TFLOPS = {"bf16": 2516.6, "fp32": 157.3}      # MI355X dense peaks
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (see profiles/); None until measured.
+ATTN_TRAFFIC_BYTES = None
+
+
+def layer_flops(cfg, plan, routes):
+    """QK^T and PV multiply-adds (2 FLOP each) each route has to do; returns per-route totals."""
+    d, N, L, Lt = cfg.head_dim, cfg.n_tokens, cfg.n_video, cfg.n_text
+    kw = plan.window_key_tiles * plan.tile_tokens
+    per_head = [4.0 * N * N * d,
+                4.0 * d * (L * (kw + Lt) + Lt * N),
+                4.0 * (plan.n_core + Lt) ** 2 * d]
+    counts = [int((routes == r).sum()) for r in range(3)]
+    return [per_head[r] * counts[r] for r in range(3)], per_head, counts
+
+
+def cpu_baseline(cfg, q, k, v, routes, total_flops, per_head_flops, counts, budget_s=20.0):
+    """Time the oracle on a few rows of one head per route and scale to the layer."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import vorta_oracle as vo
+
+    spec = vo.LayerSpec(grid=cfg.grid, tile=cfg.tile, window=cfg.window, bucket=cfg.bucket,
+                        keep_num=cfg.keep_num, keep_den=cfg.keep_den, n_text=cfg.n_text)
+    N, L = cfg.n_tokens, cfg.n_video
+    rng = np.random.default_rng(0)
+    layer_s, sample = 0.0, []
+    n_rows = {0: 512, 1: 1024, 2: 1024}
+    for r in range(3):
+        if counts[r] == 0:
+            continue
+        h = int(np.nonzero(routes == r)[0][0])
+        Q, K, V = (t[h].double().cpu().numpy() for t in (q, k, v))
+        rows = np.sort(rng.choice(N, min(n_rows[r], N), replace=False))
+        fixed = 0.0
+        t0 = time.perf_counter()
+        if r == 2:
+            index = vo.bcs_select(K[:L], cfg.grid, cfg.bucket, cfg.keep_num, cfg.keep_den)
+            fixed = time.perf_counter() - t0            # whole-head cost, not per row
+            t0 = time.perf_counter()
+            vo.coreset_attention(Q, K, V, spec, rows, index=index)
+        else:
+            vo.head_attention(r, Q, K, V, spec, rows)
+        per_row = (time.perf_counter() - t0) / len(rows)
+        # a core-set row stands for the tokens merged into it: L_c + Lt distinct rows per head
+        head_rows = (L // 2 + cfg.n_text) if r == 2 and cfg.keep_den == 2 * cfg.keep_num else N
+        layer_s += counts[r] * (fixed + per_row * head_rows)
+        sample.append(f"route {r}: {len(rows)} rows of head {h}")
+    threads = max([i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"] or [1])
+    return {"value": total_flops / layer_s / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "ms_per_layer_extrapolated": layer_s * 1e3,
+            "sample": "fp64 NumPy oracle, " + "; ".join(sample) + "; per-row time scaled to all rows and heads"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="wan720p")
+    ap.add_argument("--layout", type=int, default=1, help="1 = [heads][N][d], 0 = [N][heads][d]")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)")
+
+    import numpy as np
+    import torch
+    import paper_2505_18809_amd as vorta
+    from synth_inputs import get_config, make_qkv, make_routes
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the library has no CPU path")
+    dev = "cuda:0"
+    cfg = get_config(args.workload)
+    routes = make_routes(cfg).numpy()
+    q, k, v = make_qkv(cfg, dev, args.layout)
+    plan = vorta.plan_for(cfg, layout=args.layout)
+    out = torch.empty_like(q)
+    ws = torch.empty(vorta.vorta_workspace_bytes(plan, routes), dtype=torch.uint8, device=dev)
+    per_route, per_head, counts = layer_flops(cfg, plan, routes)
+    flops = sum(per_route)
+
+    def step():
+        vorta.vorta_routed_attention_layer(plan, q, k, v, routes, out=out, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # second pass: the same launches issued stage by stage, events around each stage
+    off = vorta.vorta_workspace_layout(plan, routes)
+    n_win, n_lr = counts[1], counts[2]
+    row = cfg.head_dim * plan.elem_bytes
+    def buf(i, heads, rows):
+        return ws[off[i]: off[i] + heads * rows * row].view(q.dtype).view(heads, rows, cfg.head_dim)
+    q_t, k_t, v_t, o_t = (buf(i, n_win, plan.n_tokens) for i in range(4))
+    q_c, k_c, v_c, o_c = (buf(i, n_lr, plan.n_core_tokens) for i in range(4, 8))
+    keep_idx = ws[off[8]: off[8] + n_lr * plan.n_core * 4].view(torch.int32).view(n_lr, plan.n_core)
+    assign = ws[off[9]: off[9] + n_lr * plan.n_video * 4].view(torch.int32).view(n_lr, plan.n_video)
+    stages = {
+        "reorder_to_tiles": lambda: [vorta.vorta_reorder_to_tiles(plan, s, routes, d) for s, d in ((q, q_t), (k, k_t), (v, v_t))],
+        "bcs_build_index": lambda: vorta.vorta_bcs_build_index(plan, k, routes, keep_idx, assign),
+        "bcs_pool": lambda: [vorta.vorta_bcs_pool(plan, s, routes, keep_idx, assign, d) for s, d in ((q, q_c), (k, k_c), (v, v_c))],
+        "attention_routed": lambda: vorta.vorta_attention_routed(plan, routes, q=q, k=k, v=v, out=out, q_t=q_t, k_t=k_t, v_t=v_t,
+                                                                  o_t=o_t, q_c=q_c, k_c=k_c, v_c=v_c, o_c=o_c),
+        "scatter_back": lambda: vorta.vorta_scatter_back(plan, routes, o_t, o_c, assign, out),
+    }
+    stage_ms = {name: 0.0 for name in stages}
+    events = []
+    for _ in range(args.steps):
+        for name, fn in stages.items():
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            events.append((name, e0, e1))
+    torch.cuda.synchronize()
+    for name, e0, e1 in events:
+        stage_ms[name] += e0.elapsed_time(e1) / args.steps
+
+    # algorithmic bytes of the memory passes (read + write of the rows each pass must move)
+    N, L, Lc = plan.n_tokens, plan.n_video, plan.n_core
+    pass_bytes = {
+        "reorder_to_tiles": 2 * 3 * n_win * N * row,
+        "bcs_build_index": n_lr * L * row + n_lr * (Lc + L) * 4,
+        "bcs_pool": 3 * n_lr * (N * row + plan.n_core_tokens * row + L * 4),
+        "scatter_back": 2 * (n_win + n_lr) * N * row + n_lr * L * 4,
+    }
+    attn_ms = stage_ms["attention_routed"]
+    peak = MFMA_PEAK_TFLOPS[cfg.dtype]
+    achieved = flops / (attn_ms * 1e-3) / 1e12
+    result = {
+        "metric": METRIC,
+        "value": flops / (ms * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms,
+        "ms_per_layer": ms,
+        "mfma_peak_frac": flops / (ms * 1e-3) / 1e12 / peak,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: grid {cfg.grid} = {cfg.n_video} video + {cfg.n_text} text tokens, "
+                               f"{cfg.heads} heads x {cfg.head_dim}, tiles {cfg.tile}, window {cfg.window} tiles, "
+                               f"bucket {cfg.bucket} r={cfg.keep_num}/{cfg.keep_den}",
+                   "routes_full_window_coreset": counts, "layout": "HND" if args.layout == 1 else "NHD",
+                   "flops_per_layer": flops},
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel" if cfg.dtype == "bf16" else "attn_f32_kernel",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "ms_per_launch": attn_ms, "traffic": ATTN_TRAFFIC_BYTES},
+        "stages_ms": stage_ms,
+        "memory_passes_GBps": {n: pass_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in pass_bytes if stage_ms[n] > 0},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, q if args.layout == 1 else q.transpose(0, 1),
+                                              k if args.layout == 1 else k.transpose(0, 1),
+                                              v if args.layout == 1 else v.transpose(0, 1),
+                                              routes, flops, per_head, counts)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,213 @@
+/*
+ * vorta.h -- C ABI of the routed attention layer of VORTA (arXiv 2505.18809)
+ * for AMD MI355X (gfx950).
+ *
+ * One layer call computes, for every head h of a video diffusion transformer
+ * attention layer, the branch its route selects (Eq. 4):
+ *     route 0  full 3-D attention                         (Eq. 2)
+ *     route 1  3-D sliding tile attention                 (Algorithm 1)
+ *     route 2  core-set attention  unpool . attn . pool   (section 3.2, Fig. 3)
+ *
+ * Conventions that hold for every call
+ *   - Tokens: the F x H x W latent grid flattened frame-major (F slowest) into
+ *     L video tokens, followed by n_text text tokens; N = L + n_text.
+ *   - Tensors are dense arrays of `dtype` elements in `layout`:
+ *     VORTA_LAYOUT_NHD = [N][heads][head_dim], VORTA_LAYOUT_HND =
+ *     [heads][N][head_dim].  "user layout" below means this.
+ *   - routes_host is a HOST array uint8[heads] with codes 0/1/2 (the router is
+ *     a scalar-sized host decision).  Heads of one route are numbered by
+ *     ascending head id ("slot"); internal per-route buffers are indexed by slot.
+ *   - Every other data pointer is DEVICE memory owned by the caller, 16-byte
+ *     aligned, alive until the stream work has finished.  The library never
+ *     frees or keeps caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Device
+ *     calls only enqueue work; they do not synchronise.  Exception: the first
+ *     device call on a plan uploads the plan's small index tables with a
+ *     blocking hipMalloc + hipMemcpy (a few hundred KB, once per plan).
+ *   - Return value: VORTA_OK or a negative error code; vorta_last_error() has
+ *     a thread-local message.  Nothing is printed, thrown or aborted.  Invalid
+ *     arguments are rejected before any kernel is launched.
+ *   - There is no CPU fallback: device calls on a machine without a usable
+ *     gfx950 device fail with VORTA_EHIP.
+ */
+#ifndef VORTA_H
+#define VORTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  VORTA_OK = 0,
+  VORTA_EINVAL = -1,      /* null pointer, bad enum value                                  */
+  VORTA_ESHAPE = -2,      /* grid not divisible by tile, window/bucket < 1, head_dim unsupported */
+  VORTA_EDTYPE = -3,
+  VORTA_EWORKSPACE = -4,  /* workspace smaller than vorta_workspace_bytes                   */
+  VORTA_EROUTE = -5,      /* a route code above 2                                          */
+  VORTA_EHIP = -6,        /* a HIP runtime call failed; message holds hipGetErrorString    */
+  VORTA_EALIGN = -7       /* a device pointer is not 16-byte aligned                       */
+};
+
+enum { VORTA_ROUTE_FULL = 0, VORTA_ROUTE_WINDOW = 1, VORTA_ROUTE_CORESET = 2 };
+enum { VORTA_F32 = 0, VORTA_BF16 = 1 };
+enum { VORTA_LAYOUT_NHD = 0, VORTA_LAYOUT_HND = 1 };
+enum { VORTA_CENTER_CLAMP = 0, VORTA_CENTER_IDENTITY = 1 };
+
+#define VORTA_MAX_HEADS 128
+
+/* Layer description: plain data, copied by vorta_plan_create. */
+typedef struct vorta_layer_desc {
+  int32_t F, H, W;          /* latent grid                                                   */
+  int32_t n_text;           /* text tokens after the video tokens (0 = none)                 */
+  int32_t heads;            /* 1 .. VORTA_MAX_HEADS                                          */
+  int32_t head_dim;         /* bf16: 128; fp32: 64 or 128                                    */
+  int32_t dtype;            /* VORTA_F32 | VORTA_BF16 (inputs, outputs and internal buffers) */
+  int32_t layout;           /* VORTA_LAYOUT_*                                                */
+  int32_t tile[3];          /* tokens per tile (t_F, t_H, t_W); must divide the grid         */
+  int32_t window[3];        /* window in TILES, the unit Algorithm 1 compares; >= 1          */
+  int32_t center_mode;      /* VORTA_CENTER_*: how get_window_center_id treats border tiles  */
+  int32_t bucket[3];        /* BCS bucket, the paper uses (2,3,2); border buckets are clipped */
+  int32_t keep_num, keep_den; /* core-set ratio r = keep_num/keep_den, 0 < r <= 1 (paper: 1/2) */
+  float softmax_scale;      /* <= 0 selects 1/sqrt(head_dim)                                 */
+} vorta_layer_desc;
+
+typedef struct vorta_plan vorta_plan;   /* opaque */
+
+typedef struct vorta_plan_info {
+  int64_t n_video;          /* L                                                             */
+  int64_t n_tokens;         /* N = L + n_text                                                */
+  int32_t tiles[3];         /* tile grid n = grid / tile                                     */
+  int32_t n_tiles;
+  int32_t tile_tokens;      /* tokens per tile                                               */
+  int32_t window_key_tiles; /* key tiles every video query sees (clamp mode; max otherwise)  */
+  int32_t max_runs;         /* row stride of the window run table                            */
+  int32_t n_buckets;
+  int64_t n_core;           /* L_c: core-set slots of the video tokens                       */
+  int64_t n_core_tokens;    /* L_c + n_text: rows of a core-set buffer                       */
+  int32_t elem_bytes;
+} vorta_plan_info;
+
+const char* vorta_strerror(int code);   /* static string                                       */
+const char* vorta_last_error(void);     /* thread-local, valid until the thread's next call    */
+
+/* ---- plan: host-side geometry of one layer ---------------------------------------------- */
+
+/* Validates desc, builds the host index tables.  No HIP call.  *out is owned by the caller
+ * and released with vorta_plan_destroy (which also frees the plan's device tables). */
+int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out);
+int vorta_plan_destroy(vorta_plan* plan);
+int vorta_plan_info_get(const vorta_plan* plan, vorta_plan_info* out);
+
+/* ---- host tables: deterministic integers, checkable without a GPU ----------------------- */
+
+/* Tile order (Algorithm 1's get_tile_id_3d made a storage order): token with raster index i
+ * goes to position perm[i] = tile_id * tile_tokens + local_id, tile ids and local ids both
+ * frame-major inside their grids.  perm: host int32[L]. */
+int vorta_tile_permutation(const vorta_plan* plan, int32_t* perm);
+
+/* Algorithm 1 per query tile: the key tiles with abs(centre_d - k_d) <= window_d / 2 form
+ * the box [lo_d, hi_d] (inclusive) returned as boxes[tile][6] = {loF,hiF,loH,hiH,loW,hiW}.
+ * boxes: host int32[n_tiles][6]. */
+int vorta_window_boxes(const vorta_plan* plan, int32_t* boxes);
+
+/* The same boxes as runs of consecutive rows of a tile-ordered buffer, plus, if n_text > 0,
+ * one run for the text rows: runs[tile][r] = {first_row, n_rows}, n_runs[tile] entries used.
+ * runs: host int32[n_tiles][max_runs][2]; n_runs: host int32[n_tiles]. */
+int vorta_window_runs(const vorta_plan* plan, int32_t* runs, int32_t* n_runs);
+
+/* BCS slot layout (section 3.2): buckets in raster order of bucket coordinates; bucket b owns
+ * core-set slots [slot_base[b], slot_base[b+1]).  slot_base: host int32[n_buckets + 1]. */
+int vorta_bcs_slot_bases(const vorta_plan* plan, int32_t* slot_base);
+
+/* Eq. 4 bookkeeping: heads_by_route lists head ids grouped by route (route 0 first, ascending
+ * id inside a group); counts[r] = heads on route r.  All host arrays. */
+int vorta_route_partition(const vorta_plan* plan, const uint8_t* routes_host,
+                          int32_t* heads_by_route, int32_t counts[3]);
+
+/* Eq. 4: gates alpha[heads][3] = (full, sliding, core-set) -> route codes; a branch is
+ * taken only if its gate strictly exceeds both others, every tie goes to full.  Host arrays. */
+int vorta_route_select(const float* alpha_host, int32_t heads, uint8_t* routes_host);
+
+/* ---- device passes ------------------------------------------------------------------------ */
+
+/* Token reorder, raster order -> tile order, for the heads on route 1 (Algorithm 1 needs
+ * tile-contiguous tokens for a block-dense mask).  src: user layout.  dst: [n_win][N][d]
+ * (slot-major; text rows copied unchanged after the L video rows). */
+int vorta_reorder_to_tiles(vorta_plan* plan, const void* src, const uint8_t* routes_host,
+                           void* dst, void* stream);
+
+/* Inverse: src [n_win][N][d] in tile order -> rows of the route-1 heads of dst (user layout,
+ * raster order).  Rows of other heads are not touched. */
+int vorta_reorder_from_tiles(vorta_plan* plan, const void* src, const uint8_t* routes_host,
+                             void* dst, void* stream);
+
+/* Bucketed core-set selection for the heads on route 2 (section 3.2, Fig. 3).  feat: user
+ * layout feature tensor (the layer call passes K).  Per bucket: cosine similarity (fp64) of
+ * the centre token to every other token, the k = floor(B (1 - r)) most similar are pruned
+ * (ties: smaller local raster index first).  Outputs, slot-major:
+ *   keep_idx int32[n_lr][L_c]  raster index of the token in each core-set slot
+ *   assign   int32[n_lr][L]    slot each token reads its output from (own slot if kept,
+ *                              its bucket centre's slot if pruned). */
+int vorta_bcs_build_index(vorta_plan* plan, const void* feat, const uint8_t* routes_host,
+                          int32_t* keep_idx, int32_t* assign, void* stream);
+
+/* pool(): dst[slot][s] = mean of src rows assigned to core-set slot s (a kept token alone,
+ * or a centre with the tokens pruned into it), then the text rows unchanged.  src: user
+ * layout; dst: [n_lr][L_c + n_text][d].  Call once per tensor (Q, K, V). */
+int vorta_bcs_pool(vorta_plan* plan, const void* src, const uint8_t* routes_host,
+                   const int32_t* keep_idx, const int32_t* assign, void* dst, void* stream);
+
+/* Buffers of the fused attention launch.  Unused groups may be NULL when no head takes
+ * that route. */
+typedef struct vorta_attn_io {
+  const void *q, *k, *v;        /* user layout; read by route-0 heads                          */
+  void* out;                    /* user layout; route-0 heads write their rows here            */
+  const void *q_t, *k_t, *v_t;  /* [n_win][N][d] tile order (vorta_reorder_to_tiles)           */
+  void* o_t;                    /* [n_win][N][d] tile order                                    */
+  const void *q_c, *k_c, *v_c;  /* [n_lr][L_c + n_text][d] (vorta_bcs_pool)                    */
+  void* o_c;                    /* [n_lr][L_c + n_text][d]                                     */
+} vorta_attn_io;
+
+/* softmax(scale * Q K^T) V for every head in ONE launch: route 0 over all N keys (Eq. 2),
+ * route 1 over the key tiles of vorta_window_runs plus text keys (Algorithm 1), route 2
+ * over the pooled core-set rows.  bf16: MFMA contractions, fp32 softmax statistics, P and
+ * the output rounded to bf16.  fp32: fp32 throughout. */
+int vorta_attention_routed(vorta_plan* plan, const uint8_t* routes_host,
+                           const vorta_attn_io* io, void* stream);
+
+/* Back to sequence order: route 1 rows by the inverse tile permutation from o_t, route 2
+ * rows by unpool() -- out[i] = o_c[assign[i]], text rows from o_c[L_c + t] -- into the
+ * user-layout out.  Route 0 rows are already in place. */
+int vorta_scatter_back(vorta_plan* plan, const uint8_t* routes_host, const void* o_t,
+                       const void* o_c, const int32_t* assign, void* out, void* stream);
+
+/* ---- the whole path ----------------------------------------------------------------------- */
+
+/* Bytes of device scratch the layer call needs for these routes (internal buffers above). */
+int vorta_workspace_bytes(const vorta_plan* plan, const uint8_t* routes_host, size_t* bytes);
+
+/* Byte offsets of the internal buffers inside the workspace, in the order
+ * q_t,k_t,v_t,o_t,q_c,k_c,v_c,o_c,keep_idx,assign (for inspection by tests). */
+int vorta_workspace_layout(const vorta_plan* plan, const uint8_t* routes_host, size_t offsets[10]);
+
+/* reorder + index build + pool + fused attention + scatter back, all on `stream`:
+ * q, k, v (user layout) -> out (user layout).  The BCS feature is K. */
+int vorta_routed_attention_layer(vorta_plan* plan, const void* q, const void* k, const void* v,
+                                 const uint8_t* routes_host, void* out, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/* Eq. 5 (router optimisation forward): every head runs all three branches and the outputs
+ * are blended with its gates, out = a1 attn + a2 sliding + a3 coreset.  alpha_host:
+ * host float[heads][3].  workspace: vorta_soft_mixture_workspace_bytes. */
+int vorta_soft_mixture_workspace_bytes(const vorta_plan* plan, size_t* bytes);
+int vorta_soft_mixture_layer(vorta_plan* plan, const void* q, const void* k, const void* v,
+                             const float* alpha_host, void* out, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VORTA_H */

@@ -1,0 +1,227 @@
+// Device entry points of libvorta: argument checks, workspace carving, launch sequencing.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "vorta_attn_common.h"
+
+namespace vorta {
+
+static int check_ptr(const void* p, const char* name) {
+  if (!p) return fail(VORTA_EINVAL, "%s is null", name);
+  if ((uintptr_t)p & 15) return fail(VORTA_EALIGN, "%s = %p is not 16-byte aligned", name, p);
+  return VORTA_OK;
+}
+
+#define VORTA_TRY(expr)        \
+  do {                         \
+    if (int rc_ = (expr)) return rc_; \
+  } while (0)
+
+static int begin(vorta_plan* p, const uint8_t* routes, RouteLists* rl) {
+  clear_error();
+  VORTA_TRY(split_routes(p, routes, rl));
+  return ensure_device_tables(p);
+}
+
+int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, AttnArgs* a) {
+  std::memset(a, 0, sizeof(*a));
+  const UserTensor ut = user_tensor(p, io->q);
+  a->q0 = io->q; a->k0 = io->k; a->v0 = io->v; a->o0 = io->out;
+  a->head_stride0 = ut.head_stride;
+  a->row_stride0 = ut.row_stride;
+  a->qc = io->q_c; a->kc = io->k_c; a->vc = io->v_c; a->oc = io->o_c;
+  a->qt = io->q_t; a->kt = io->k_t; a->vt = io->v_t; a->ot = io->o_t;
+  a->runs = p->d_runs;
+  a->n_runs = p->d_n_runs;
+  a->max_runs = p->max_runs;
+  a->N = (int)p->N;
+  a->Nc = (int)(p->Lc + p->d.n_text);
+  a->L = (int)p->L;
+  a->n_text = p->d.n_text;
+  a->n_tiles = p->n_tiles;
+  a->tile_tokens = p->tile_tokens;
+  a->qb_dense = (a->N + BM - 1) / BM;
+  a->qb_core = (a->Nc + BM - 1) / BM;
+  a->qb_tile = (a->tile_tokens + BM - 1) / BM;
+  a->qb_text = (a->n_text + BM - 1) / BM;
+  const long end_dense = (long)rl.count[0] * a->qb_dense;
+  const long end_core = end_dense + (long)rl.count[2] * a->qb_core;
+  const long end_tile = end_core + (long)rl.count[1] * a->n_tiles * a->qb_tile;
+  const long end_text = end_tile + (long)rl.count[1] * a->qb_text;
+  if (end_text > 0x7fffffffL) return fail(VORTA_ESHAPE, "%ld work items exceed the grid limit", end_text);
+  a->end_dense = (int)end_dense;
+  a->end_core = (int)end_core;
+  a->end_tile = (int)end_tile;
+  a->end_text = (int)end_text;
+  a->scale = p->scale;
+  for (int i = 0; i < rl.count[0]; ++i) a->dense_heads[i] = (uint8_t)rl.heads[0][i];
+  return VORTA_OK;
+}
+
+static int attention(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream) {
+  if (!io) return fail(VORTA_EINVAL, "io is null");
+  if (rl.count[0]) {
+    VORTA_TRY(check_ptr(io->q, "io.q")); VORTA_TRY(check_ptr(io->k, "io.k"));
+    VORTA_TRY(check_ptr(io->v, "io.v")); VORTA_TRY(check_ptr(io->out, "io.out"));
+  }
+  if (rl.count[1]) {
+    VORTA_TRY(check_ptr(io->q_t, "io.q_t")); VORTA_TRY(check_ptr(io->k_t, "io.k_t"));
+    VORTA_TRY(check_ptr(io->v_t, "io.v_t")); VORTA_TRY(check_ptr(io->o_t, "io.o_t"));
+  }
+  if (rl.count[2]) {
+    VORTA_TRY(check_ptr(io->q_c, "io.q_c")); VORTA_TRY(check_ptr(io->k_c, "io.k_c"));
+    VORTA_TRY(check_ptr(io->v_c, "io.v_c")); VORTA_TRY(check_ptr(io->o_c, "io.o_c"));
+  }
+  return p->d.dtype == VORTA_BF16 ? launch_attention_bf16(p, rl, io, stream)
+                                  : launch_attention_f32(p, rl, io, stream);
+}
+
+struct Carved {
+  char* buf[10];
+};
+
+static int carve(const vorta_plan* p, const uint8_t* routes, void* workspace, size_t bytes, Carved* c) {
+  size_t need = 0, off[10];
+  VORTA_TRY(vorta_workspace_bytes(p, routes, &need));
+  if (bytes < need) return fail(VORTA_EWORKSPACE, "workspace has %zu bytes, need %zu", bytes, need);
+  VORTA_TRY(check_ptr(workspace, "workspace"));
+  VORTA_TRY(vorta_workspace_layout(p, routes, off));
+  for (int i = 0; i < 10; ++i) c->buf[i] = (char*)workspace + off[i];
+  return VORTA_OK;
+}
+
+static int layer(vorta_plan* p, const RouteLists& rl, const void* q, const void* k, const void* v,
+                 const uint8_t* routes, void* out, const Carved& c, void* stream) {
+  int32_t* keep_idx = (int32_t*)c.buf[8];
+  int32_t* assign = (int32_t*)c.buf[9];
+  // route 1: tokens into 3-D tile order
+  VORTA_TRY(launch_reorder(p, rl, q, c.buf[0], true, stream));
+  VORTA_TRY(launch_reorder(p, rl, k, c.buf[1], true, stream));
+  VORTA_TRY(launch_reorder(p, rl, v, c.buf[2], true, stream));
+  // route 2: core-set index on K, then pool Q, K, V
+  VORTA_TRY(launch_bcs_index(p, rl, k, keep_idx, assign, stream));
+  VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, c.buf[4], stream));
+  VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, c.buf[5], stream));
+  VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, c.buf[6], stream));
+  vorta_attn_io io;
+  io.q = q; io.k = k; io.v = v; io.out = out;
+  io.q_t = c.buf[0]; io.k_t = c.buf[1]; io.v_t = c.buf[2]; io.o_t = c.buf[3];
+  io.q_c = c.buf[4]; io.k_c = c.buf[5]; io.v_c = c.buf[6]; io.o_c = c.buf[7];
+  VORTA_TRY(attention(p, rl, &io, stream));
+  VORTA_TRY(launch_reorder(p, rl, out, c.buf[3], false, stream));
+  VORTA_TRY(launch_unpool(p, rl, c.buf[7], assign, out, stream));
+  (void)routes;
+  return VORTA_OK;
+}
+
+}  // namespace vorta
+
+using namespace vorta;
+
+extern "C" {
+
+int vorta_reorder_to_tiles(vorta_plan* p, const void* src, const uint8_t* routes, void* dst, void* stream) {
+  RouteLists rl;
+  VORTA_TRY(begin(p, routes, &rl));
+  if (!rl.count[1]) return VORTA_OK;
+  VORTA_TRY(check_ptr(src, "src"));
+  VORTA_TRY(check_ptr(dst, "dst"));
+  return launch_reorder(p, rl, src, dst, true, stream);
+}
+
+int vorta_reorder_from_tiles(vorta_plan* p, const void* src, const uint8_t* routes, void* dst, void* stream) {
+  RouteLists rl;
+  VORTA_TRY(begin(p, routes, &rl));
+  if (!rl.count[1]) return VORTA_OK;
+  VORTA_TRY(check_ptr(src, "src"));
+  VORTA_TRY(check_ptr(dst, "dst"));
+  return launch_reorder(p, rl, dst, const_cast<void*>(src), false, stream);
+}
+
+int vorta_bcs_build_index(vorta_plan* p, const void* feat, const uint8_t* routes, int32_t* keep_idx,
+                          int32_t* assign, void* stream) {
+  RouteLists rl;
+  VORTA_TRY(begin(p, routes, &rl));
+  if (!rl.count[2]) return VORTA_OK;
+  VORTA_TRY(check_ptr(feat, "feat"));
+  VORTA_TRY(check_ptr(keep_idx, "keep_idx"));
+  VORTA_TRY(check_ptr(assign, "assign"));
+  return launch_bcs_index(p, rl, feat, keep_idx, assign, stream);
+}
+
+int vorta_bcs_pool(vorta_plan* p, const void* src, const uint8_t* routes, const int32_t* keep_idx,
+                   const int32_t* assign, void* dst, void* stream) {
+  RouteLists rl;
+  VORTA_TRY(begin(p, routes, &rl));
+  if (!rl.count[2]) return VORTA_OK;
+  VORTA_TRY(check_ptr(src, "src"));
+  VORTA_TRY(check_ptr(keep_idx, "keep_idx"));
+  VORTA_TRY(check_ptr(assign, "assign"));
+  VORTA_TRY(check_ptr(dst, "dst"));
+  return launch_bcs_pool(p, rl, src, keep_idx, assign, dst, stream);
+}
+
+int vorta_attention_routed(vorta_plan* p, const uint8_t* routes, const vorta_attn_io* io, void* stream) {
+  RouteLists rl;
+  VORTA_TRY(begin(p, routes, &rl));
+  return attention(p, rl, io, stream);
+}
+
+int vorta_scatter_back(vorta_plan* p, const uint8_t* routes, const void* o_t, const void* o_c,
+                       const int32_t* assign, void* out, void* stream) {
+  RouteLists rl;
+  VORTA_TRY(begin(p, routes, &rl));
+  if (rl.count[1] || rl.count[2]) VORTA_TRY(check_ptr(out, "out"));
+  if (rl.count[1]) {
+    VORTA_TRY(check_ptr(o_t, "o_t"));
+    VORTA_TRY(launch_reorder(p, rl, out, const_cast<void*>(o_t), false, stream));
+  }
+  if (rl.count[2]) {
+    VORTA_TRY(check_ptr(o_c, "o_c"));
+    VORTA_TRY(check_ptr(assign, "assign"));
+    VORTA_TRY(launch_unpool(p, rl, o_c, assign, out, stream));
+  }
+  return VORTA_OK;
+}
+
+int vorta_routed_attention_layer(vorta_plan* p, const void* q, const void* k, const void* v,
+                                 const uint8_t* routes, void* out, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  RouteLists rl;
+  VORTA_TRY(begin(p, routes, &rl));
+  VORTA_TRY(check_ptr(q, "q")); VORTA_TRY(check_ptr(k, "k"));
+  VORTA_TRY(check_ptr(v, "v")); VORTA_TRY(check_ptr(out, "out"));
+  Carved c;
+  VORTA_TRY(carve(p, routes, workspace, workspace_bytes, &c));
+  return layer(p, rl, q, k, v, routes, out, c, stream);
+}
+
+int vorta_soft_mixture_layer(vorta_plan* p, const void* q, const void* k, const void* v,
+                             const float* alpha_host, void* out, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  clear_error();
+  if (!p || !alpha_host) return fail(VORTA_EINVAL, "null plan or alpha");
+  VORTA_TRY(check_ptr(q, "q")); VORTA_TRY(check_ptr(k, "k"));
+  VORTA_TRY(check_ptr(v, "v")); VORTA_TRY(check_ptr(out, "out"));
+  size_t need = 0;
+  VORTA_TRY(vorta_soft_mixture_workspace_bytes(p, &need));
+  if (workspace_bytes < need) return fail(VORTA_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, need);
+  VORTA_TRY(check_ptr(workspace, "workspace"));
+  const size_t out_bytes = ((size_t)p->d.heads * p->N * p->d.head_dim * p->elem_bytes + 255) & ~(size_t)255;
+  char* branch[3] = {(char*)workspace, (char*)workspace + out_bytes, (char*)workspace + 2 * out_bytes};
+  char* inner = (char*)workspace + 3 * out_bytes;
+  const size_t inner_bytes = workspace_bytes - 3 * out_bytes;
+  uint8_t routes[VORTA_MAX_HEADS];
+  for (int r = 0; r < 3; ++r) {
+    std::memset(routes, r, sizeof(routes));
+    RouteLists rl;
+    VORTA_TRY(begin(p, routes, &rl));
+    Carved c;
+    VORTA_TRY(carve(p, routes, inner, inner_bytes, &c));
+    VORTA_TRY(layer(p, rl, q, k, v, routes, branch[r], c, stream));
+  }
+  return launch_blend3(p, branch[0], branch[1], branch[2], alpha_host, out, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,101 @@
+// Work decomposition shared by the attention kernels.
+//
+// One launch covers every head of the layer.  Its grid is four consecutive segments of
+// work items, longest items first so the short ones fill the tail of the launch:
+//   [ route 0: (head, q-block) over all N rows            | keys: rows [0, N) of the head      ]
+//   [ route 2: (slot, q-block) over L_c + n_text rows     | keys: all rows of the core-set     ]
+//   [ route 1: (slot, tile, q-block inside the tile)      | keys: the tile's run list          ]
+//   [ route 1: (slot, q-block over the text rows)         | keys: rows [0, N)                  ]
+// A work item is BM query rows; its keys are a short list of runs of consecutive rows.
+#pragma once
+
+#include <cstdint>
+
+#include "vorta_internal.h"
+
+namespace vorta {
+
+struct AttnArgs {
+  // route 0: caller's tensors
+  const void *q0, *k0, *v0;
+  void* o0;
+  long head_stride0, row_stride0;   // elements
+  // route 2: [n_lr][Nc][d]
+  const void *qc, *kc, *vc;
+  void* oc;
+  // route 1: [n_win][N][d] in tile order
+  const void *qt, *kt, *vt;
+  void* ot;
+  const int* runs;                  // [n_tiles][max_runs][2]
+  const int* n_runs;                // [n_tiles]
+  int max_runs;
+  int N, Nc, L, n_text;
+  int n_tiles, tile_tokens;
+  int qb_dense, qb_core, qb_tile, qb_text;   // q-blocks per head / core-set / tile / text part
+  int end_dense, end_core, end_tile, end_text;   // cumulative item counts
+  float scale;
+  uint8_t dense_heads[VORTA_MAX_HEADS];
+};
+
+struct WorkItem {
+  long q_off, kv_off, o_off;   // element offsets of the head's row 0 in q / k,v / o
+  long row_stride;             // elements
+  int seg;                     // 0 dense, 1 core-set, 2 window
+  int row0, n_rows;            // query rows [row0, row0 + n_rows)
+  int n_runs;
+  const int* runs;             // null: the single run {0, single_len}
+  int single_len;
+};
+
+template <int BM, int D>
+__device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
+  WorkItem w;
+  w.runs = nullptr;
+  w.n_runs = 1;
+  if (item < a.end_dense) {
+    const int slot = item / a.qb_dense, qb = item - slot * a.qb_dense;
+    w.seg = 0;
+    w.q_off = w.kv_off = w.o_off = a.dense_heads[slot] * a.head_stride0;
+    w.row_stride = a.row_stride0;
+    w.row0 = qb * BM;
+    w.n_rows = min(BM, a.N - w.row0);
+    w.single_len = a.N;
+  } else if (item < a.end_core) {
+    item -= a.end_dense;
+    const int slot = item / a.qb_core, qb = item - slot * a.qb_core;
+    w.seg = 1;
+    w.q_off = w.kv_off = w.o_off = (long)slot * a.Nc * D;
+    w.row_stride = D;
+    w.row0 = qb * BM;
+    w.n_rows = min(BM, a.Nc - w.row0);
+    w.single_len = a.Nc;
+  } else if (item < a.end_tile) {
+    item -= a.end_core;
+    const int per_head = a.n_tiles * a.qb_tile;
+    const int slot = item / per_head, r = item - slot * per_head;
+    const int tile = r / a.qb_tile, qb = r - tile * a.qb_tile;
+    w.seg = 2;
+    w.q_off = w.kv_off = w.o_off = (long)slot * a.N * D;
+    w.row_stride = D;
+    w.row0 = tile * a.tile_tokens + qb * BM;
+    w.n_rows = min(BM, a.tile_tokens - qb * BM);
+    w.runs = a.runs + (long)tile * a.max_runs * 2;
+    w.n_runs = a.n_runs[tile];
+    w.single_len = 0;
+  } else {
+    item -= a.end_tile;
+    const int slot = item / a.qb_text, qb = item - slot * a.qb_text;
+    w.seg = 2;
+    w.q_off = w.kv_off = w.o_off = (long)slot * a.N * D;
+    w.row_stride = D;
+    w.row0 = a.L + qb * BM;
+    w.n_rows = min(BM, a.n_text - qb * BM);
+    w.single_len = a.N;
+  }
+  return w;
+}
+
+// Fills everything of AttnArgs that does not depend on the kernel's block size.
+int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, AttnArgs* a);
+
+}  // namespace vorta

@@ -1,0 +1,332 @@
+// Host side of libvorta: plan construction, integer index tables, route bookkeeping.
+// Nothing in this file touches the GPU.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "vorta_internal.h"
+
+namespace vorta {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+void clear_error() { g_err[0] = 0; }
+
+int split_routes(const vorta_plan* p, const uint8_t* routes, RouteLists* out) {
+  if (!p || !routes || !out) return fail(VORTA_EINVAL, "null plan or routes");
+  *out = RouteLists();
+  for (int h = 0; h < p->d.heads; ++h) {
+    int r = routes[h];
+    if (r > 2) return fail(VORTA_EROUTE, "routes[%d] = %d, expected 0, 1 or 2", h, r);
+    out->heads[r][out->count[r]++] = h;
+  }
+  return VORTA_OK;
+}
+
+UserTensor user_tensor(const vorta_plan* p, const void* base) {
+  UserTensor t;
+  t.base = base;
+  const int64_t d = p->d.head_dim;
+  if (p->d.layout == VORTA_LAYOUT_NHD) {
+    t.head_stride = d;
+    t.row_stride = (int64_t)p->d.heads * d;
+  } else {
+    t.head_stride = p->N * d;
+    t.row_stride = d;
+  }
+  return t;
+}
+
+}  // namespace vorta
+
+using namespace vorta;
+
+extern "C" {
+
+const char* vorta_strerror(int code) {
+  switch (code) {
+    case VORTA_OK: return "ok";
+    case VORTA_EINVAL: return "invalid argument";
+    case VORTA_ESHAPE: return "unsupported shape";
+    case VORTA_EDTYPE: return "unsupported dtype";
+    case VORTA_EWORKSPACE: return "workspace too small";
+    case VORTA_EROUTE: return "invalid route code";
+    case VORTA_EHIP: return "HIP runtime error";
+    case VORTA_EALIGN: return "pointer not 16-byte aligned";
+    default: return "unknown error";
+  }
+}
+
+const char* vorta_last_error(void) { return g_err; }
+
+// Window centre of Algorithm 1's get_window_center_id: "clamp" keeps the window inside the
+// tile grid, "identity" leaves the query tile as the centre.
+static int window_centre(int q, int n, int w, int mode) {
+  if (mode == VORTA_CENTER_IDENTITY) return q;
+  const int half = w / 2;
+  const int lo = half, hi = std::max(n - 1 - half, half);
+  return std::min(std::max(q, lo), hi);
+}
+
+int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
+  clear_error();
+  if (!desc || !out) return fail(VORTA_EINVAL, "null desc or out");
+  *out = nullptr;
+  const vorta_layer_desc& d = *desc;
+  if (d.F < 1 || d.H < 1 || d.W < 1 || d.n_text < 0)
+    return fail(VORTA_ESHAPE, "grid %dx%dx%d / n_text %d must be positive", d.F, d.H, d.W, d.n_text);
+  if ((int64_t)d.F * d.H * d.W + d.n_text > (int64_t)1 << 30)
+    return fail(VORTA_ESHAPE, "more than 2^30 tokens");
+  if (d.heads < 1 || d.heads > VORTA_MAX_HEADS)
+    return fail(VORTA_ESHAPE, "heads = %d, supported 1..%d", d.heads, VORTA_MAX_HEADS);
+  if (d.dtype != VORTA_F32 && d.dtype != VORTA_BF16) return fail(VORTA_EDTYPE, "dtype %d", d.dtype);
+  if (d.dtype == VORTA_BF16 && d.head_dim != 128)
+    return fail(VORTA_ESHAPE, "bf16 supports head_dim 128, got %d", d.head_dim);
+  if (d.dtype == VORTA_F32 && d.head_dim != 64 && d.head_dim != 128)
+    return fail(VORTA_ESHAPE, "fp32 supports head_dim 64 or 128, got %d", d.head_dim);
+  if (d.layout != VORTA_LAYOUT_NHD && d.layout != VORTA_LAYOUT_HND)
+    return fail(VORTA_EINVAL, "layout %d", d.layout);
+  if (d.center_mode != VORTA_CENTER_CLAMP && d.center_mode != VORTA_CENTER_IDENTITY)
+    return fail(VORTA_EINVAL, "center_mode %d", d.center_mode);
+  const int grid[3] = {d.F, d.H, d.W};
+  int64_t bucket_tokens = 1;
+  for (int a = 0; a < 3; ++a) {
+    if (d.tile[a] < 1 || grid[a] % d.tile[a])
+      return fail(VORTA_ESHAPE, "tile[%d] = %d does not divide grid %d", a, d.tile[a], grid[a]);
+    if (d.window[a] < 1) return fail(VORTA_ESHAPE, "window[%d] = %d < 1", a, d.window[a]);
+    if (d.bucket[a] < 1) return fail(VORTA_ESHAPE, "bucket[%d] = %d < 1", a, d.bucket[a]);
+    bucket_tokens *= d.bucket[a];
+  }
+  if (bucket_tokens > 64) return fail(VORTA_ESHAPE, "bucket holds %lld tokens, at most 64", (long long)bucket_tokens);
+  if (d.keep_num < 1 || d.keep_den < d.keep_num)
+    return fail(VORTA_ESHAPE, "core-set ratio %d/%d outside (0, 1]", d.keep_num, d.keep_den);
+
+  vorta_plan* p = new (std::nothrow) vorta_plan();
+  if (!p) return fail(VORTA_EINVAL, "out of host memory");
+  p->d = d;
+  p->L = (int64_t)d.F * d.H * d.W;
+  p->N = p->L + d.n_text;
+  p->elem_bytes = d.dtype == VORTA_BF16 ? 2 : 4;
+  p->scale = d.softmax_scale > 0.f ? d.softmax_scale : (float)(1.0 / std::sqrt((double)d.head_dim));
+  p->tile_tokens = d.tile[0] * d.tile[1] * d.tile[2];
+  for (int a = 0; a < 3; ++a) {
+    p->nt[a] = grid[a] / d.tile[a];
+    p->nb[a] = (grid[a] + d.bucket[a] - 1) / d.bucket[a];
+  }
+  p->n_tiles = p->nt[0] * p->nt[1] * p->nt[2];
+  p->n_buckets = p->nb[0] * p->nb[1] * p->nb[2];
+
+  // Algorithm 1: key-tile box of every query tile.
+  p->boxes.resize((size_t)p->n_tiles * 6);
+  std::vector<std::vector<int32_t>> run_lists(p->n_tiles);
+  p->window_key_tiles = 0;
+  for (int qf = 0; qf < p->nt[0]; ++qf)
+    for (int qh = 0; qh < p->nt[1]; ++qh)
+      for (int qw = 0; qw < p->nt[2]; ++qw) {
+        const int q[3] = {qf, qh, qw};
+        const int tile = (qf * p->nt[1] + qh) * p->nt[2] + qw;
+        int lo[3], hi[3];
+        for (int a = 0; a < 3; ++a) {
+          const int c = window_centre(q[a], p->nt[a], d.window[a], d.center_mode);
+          const int half = d.window[a] / 2;   // abs(c - k) is an integer: <= w/2  <=>  <= floor(w/2)
+          lo[a] = std::max(c - half, 0);
+          hi[a] = std::min(c + half, p->nt[a] - 1);
+          p->boxes[(size_t)tile * 6 + 2 * a] = lo[a];
+          p->boxes[(size_t)tile * 6 + 2 * a + 1] = hi[a];
+        }
+        p->window_key_tiles = std::max(p->window_key_tiles,
+                                       (hi[0] - lo[0] + 1) * (hi[1] - lo[1] + 1) * (hi[2] - lo[2] + 1));
+        // Rows of a tile-ordered buffer: tiles along W are adjacent, so each (kf, kh) pair of
+        // the box is one run; adjacent runs are merged.
+        std::vector<int32_t>& rl = run_lists[tile];
+        auto push = [&rl](int64_t start, int64_t len) {
+          if (!rl.empty() && (int64_t)rl[rl.size() - 2] + rl[rl.size() - 1] == start) {
+            rl[rl.size() - 1] += (int32_t)len;
+          } else {
+            rl.push_back((int32_t)start);
+            rl.push_back((int32_t)len);
+          }
+        };
+        for (int kf = lo[0]; kf <= hi[0]; ++kf)
+          for (int kh = lo[1]; kh <= hi[1]; ++kh) {
+            const int64_t first = ((int64_t)(kf * p->nt[1] + kh) * p->nt[2] + lo[2]) * p->tile_tokens;
+            push(first, (int64_t)(hi[2] - lo[2] + 1) * p->tile_tokens);
+          }
+        if (d.n_text > 0) push(p->L, d.n_text);
+      }
+  p->max_runs = 1;
+  for (auto& rl : run_lists) p->max_runs = std::max(p->max_runs, (int)rl.size() / 2);
+  p->runs.assign((size_t)p->n_tiles * p->max_runs * 2, 0);
+  p->n_runs.resize(p->n_tiles);
+  for (int t = 0; t < p->n_tiles; ++t) {
+    p->n_runs[t] = (int32_t)run_lists[t].size() / 2;
+    std::copy(run_lists[t].begin(), run_lists[t].end(), p->runs.begin() + (size_t)t * p->max_runs * 2);
+  }
+
+  // BCS slot layout: a (border-clipped) bucket of B' tokens keeps B' - k of them,
+  // k = min(B' - 1, floor(B' (den - num) / den)).
+  p->slot_base.resize((size_t)p->n_buckets + 1);
+  int64_t slot = 0;
+  int b = 0;
+  for (int f0 = 0; f0 < d.F; f0 += d.bucket[0])
+    for (int h0 = 0; h0 < d.H; h0 += d.bucket[1])
+      for (int w0 = 0; w0 < d.W; w0 += d.bucket[2]) {
+        const int B = std::min(d.bucket[0], d.F - f0) * std::min(d.bucket[1], d.H - h0) *
+                      std::min(d.bucket[2], d.W - w0);
+        const int k = std::min(B - 1, (int)(((int64_t)B * (d.keep_den - d.keep_num)) / d.keep_den));
+        p->slot_base[b++] = (int32_t)slot;
+        slot += B - k;
+      }
+  p->slot_base[b] = (int32_t)slot;
+  p->Lc = slot;
+  *out = p;
+  return VORTA_OK;
+}
+
+int vorta_plan_info_get(const vorta_plan* p, vorta_plan_info* out) {
+  clear_error();
+  if (!p || !out) return fail(VORTA_EINVAL, "null plan or out");
+  out->n_video = p->L;
+  out->n_tokens = p->N;
+  for (int a = 0; a < 3; ++a) out->tiles[a] = p->nt[a];
+  out->n_tiles = p->n_tiles;
+  out->tile_tokens = p->tile_tokens;
+  out->window_key_tiles = p->window_key_tiles;
+  out->max_runs = p->max_runs;
+  out->n_buckets = p->n_buckets;
+  out->n_core = p->Lc;
+  out->n_core_tokens = p->Lc + p->d.n_text;
+  out->elem_bytes = p->elem_bytes;
+  return VORTA_OK;
+}
+
+int vorta_tile_permutation(const vorta_plan* p, int32_t* perm) {
+  clear_error();
+  if (!p || !perm) return fail(VORTA_EINVAL, "null plan or perm");
+  const vorta_layer_desc& d = p->d;
+  int64_t i = 0;
+  for (int f = 0; f < d.F; ++f)
+    for (int h = 0; h < d.H; ++h)
+      for (int w = 0; w < d.W; ++w, ++i) {
+        const int tile = ((f / d.tile[0]) * p->nt[1] + h / d.tile[1]) * p->nt[2] + w / d.tile[2];
+        const int local = ((f % d.tile[0]) * d.tile[1] + h % d.tile[1]) * d.tile[2] + w % d.tile[2];
+        perm[i] = tile * p->tile_tokens + local;
+      }
+  return VORTA_OK;
+}
+
+int vorta_window_boxes(const vorta_plan* p, int32_t* boxes) {
+  clear_error();
+  if (!p || !boxes) return fail(VORTA_EINVAL, "null plan or boxes");
+  std::copy(p->boxes.begin(), p->boxes.end(), boxes);
+  return VORTA_OK;
+}
+
+int vorta_window_runs(const vorta_plan* p, int32_t* runs, int32_t* n_runs) {
+  clear_error();
+  if (!p || !runs || !n_runs) return fail(VORTA_EINVAL, "null argument");
+  std::copy(p->runs.begin(), p->runs.end(), runs);
+  std::copy(p->n_runs.begin(), p->n_runs.end(), n_runs);
+  return VORTA_OK;
+}
+
+int vorta_bcs_slot_bases(const vorta_plan* p, int32_t* slot_base) {
+  clear_error();
+  if (!p || !slot_base) return fail(VORTA_EINVAL, "null argument");
+  std::copy(p->slot_base.begin(), p->slot_base.end(), slot_base);
+  return VORTA_OK;
+}
+
+int vorta_route_partition(const vorta_plan* p, const uint8_t* routes_host, int32_t* heads_by_route,
+                          int32_t counts[3]) {
+  clear_error();
+  if (!heads_by_route || !counts) return fail(VORTA_EINVAL, "null output");
+  RouteLists rl;
+  if (int rc = split_routes(p, routes_host, &rl)) return rc;
+  int n = 0;
+  for (int r = 0; r < 3; ++r) {
+    counts[r] = rl.count[r];
+    for (int i = 0; i < rl.count[r]; ++i) heads_by_route[n++] = rl.heads[r][i];
+  }
+  return VORTA_OK;
+}
+
+int vorta_route_select(const float* alpha, int32_t heads, uint8_t* routes) {
+  clear_error();
+  if (!alpha || !routes || heads < 0) return fail(VORTA_EINVAL, "null argument");
+  for (int h = 0; h < heads; ++h) {
+    const float a1 = alpha[3 * h], a2 = alpha[3 * h + 1], a3 = alpha[3 * h + 2];
+    uint8_t r = VORTA_ROUTE_FULL;
+    if (a2 > a1 && a2 > a3) r = VORTA_ROUTE_WINDOW;
+    else if (a3 > a1 && a3 > a2) r = VORTA_ROUTE_CORESET;
+    routes[h] = r;
+  }
+  return VORTA_OK;
+}
+
+// Workspace: q_t,k_t,v_t,o_t,q_c,k_c,v_c,o_c,keep_idx,assign, each 256-byte aligned.
+static void workspace_sizes(const vorta_plan* p, const RouteLists& rl, size_t sizes[10]) {
+  const size_t row = (size_t)p->d.head_dim * p->elem_bytes;
+  const size_t tiled = (size_t)rl.count[1] * p->N * row;
+  const size_t core = (size_t)rl.count[2] * (p->Lc + p->d.n_text) * row;
+  for (int i = 0; i < 4; ++i) sizes[i] = tiled;
+  for (int i = 4; i < 8; ++i) sizes[i] = core;
+  sizes[8] = (size_t)rl.count[2] * p->Lc * sizeof(int32_t);
+  sizes[9] = (size_t)rl.count[2] * p->L * sizeof(int32_t);
+}
+
+int vorta_workspace_layout(const vorta_plan* p, const uint8_t* routes_host, size_t offsets[10]) {
+  clear_error();
+  if (!offsets) return fail(VORTA_EINVAL, "null offsets");
+  RouteLists rl;
+  if (int rc = split_routes(p, routes_host, &rl)) return rc;
+  size_t sizes[10], off = 0;
+  workspace_sizes(p, rl, sizes);
+  for (int i = 0; i < 10; ++i) {
+    offsets[i] = off;
+    off += (sizes[i] + 255) & ~(size_t)255;
+  }
+  return VORTA_OK;
+}
+
+int vorta_workspace_bytes(const vorta_plan* p, const uint8_t* routes_host, size_t* bytes) {
+  clear_error();
+  if (!bytes) return fail(VORTA_EINVAL, "null bytes");
+  RouteLists rl;
+  if (int rc = split_routes(p, routes_host, &rl)) return rc;
+  size_t sizes[10], off = 0;
+  workspace_sizes(p, rl, sizes);
+  for (int i = 0; i < 10; ++i) off += (sizes[i] + 255) & ~(size_t)255;
+  *bytes = off + 256;   // never zero, so callers can always allocate it
+  return VORTA_OK;
+}
+
+int vorta_soft_mixture_workspace_bytes(const vorta_plan* p, size_t* bytes) {
+  clear_error();
+  if (!p || !bytes) return fail(VORTA_EINVAL, "null argument");
+  // the largest single-route workspace + two extra user-layout outputs
+  size_t most = 0;
+  uint8_t routes[VORTA_MAX_HEADS];
+  for (int r = 0; r < 3; ++r) {
+    std::memset(routes, r, sizeof(routes));
+    size_t b = 0;
+    if (int rc = vorta_workspace_bytes(p, routes, &b)) return rc;
+    most = std::max(most, b);
+  }
+  const size_t out_bytes = ((size_t)p->d.heads * p->N * p->d.head_dim * p->elem_bytes + 255) & ~(size_t)255;
+  *bytes = most + 3 * out_bytes;
+  return VORTA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,70 @@
+// Internal declarations shared by the translation units of libvorta.
+#pragma once
+
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "vorta.h"
+
+struct vorta_plan {
+  vorta_layer_desc d;
+  int64_t L = 0, N = 0;          // video tokens, all tokens
+  int nt[3] = {0, 0, 0};         // tile grid
+  int n_tiles = 0, tile_tokens = 0;
+  int nb[3] = {0, 0, 0};         // bucket grid (ceil)
+  int n_buckets = 0;
+  int64_t Lc = 0;                // core-set slots
+  int max_runs = 0;
+  int window_key_tiles = 0;
+  int elem_bytes = 0;
+  float scale = 0.f;
+  std::vector<int32_t> boxes;    // [n_tiles][6]
+  std::vector<int32_t> runs;     // [n_tiles][max_runs][2]
+  std::vector<int32_t> n_runs;   // [n_tiles]
+  std::vector<int32_t> slot_base;  // [n_buckets + 1]
+
+  // device copies of runs / n_runs / slot_base, uploaded on first device use
+  std::mutex mu;
+  bool on_device = false;
+  int device = -1;
+  int32_t* d_runs = nullptr;
+  int32_t* d_n_runs = nullptr;
+  int32_t* d_slot_base = nullptr;
+};
+
+namespace vorta {
+
+int fail(int code, const char* fmt, ...);        // records the thread-local message, returns code
+void clear_error();
+
+struct RouteLists {
+  int count[3] = {0, 0, 0};
+  int heads[3][VORTA_MAX_HEADS];                 // head ids per route, ascending
+};
+int split_routes(const vorta_plan* p, const uint8_t* routes, RouteLists* out);
+
+int ensure_device_tables(vorta_plan* p);         // vorta_device.hip
+
+// Launchers (each returns VORTA_OK / VORTA_EHIP).  Pointers are device memory.
+struct UserTensor {                               // a tensor in the caller's layout
+  const void* base;
+  int64_t head_stride;                            // elements
+  int64_t row_stride;                             // elements
+};
+UserTensor user_tensor(const vorta_plan* p, const void* base);
+
+int launch_reorder(vorta_plan* p, const RouteLists& rl, const void* user, void* tiled, bool to_tiles,
+                   void* stream);
+int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const void* feat, int32_t* keep_idx,
+                     int32_t* assign, void* stream);
+int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const int32_t* keep_idx,
+                    const int32_t* assign, void* dst, void* stream);
+int launch_unpool(vorta_plan* p, const RouteLists& rl, const void* o_c, const int32_t* assign, void* out,
+                  void* stream);
+int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream);
+int launch_attention_f32(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream);
+int launch_blend3(vorta_plan* p, const void* o0, const void* o1, const void* o2, const float* alpha_host,
+                  void* out, void* stream);
+
+}  // namespace vorta

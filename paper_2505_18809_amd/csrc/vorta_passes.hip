@@ -1,0 +1,443 @@
+// Memory-bound passes of the routed attention layer for gfx950: token reorder to / from
+// 3-D tile order, bucketed core-set selection (index build), pool / merge, unpool, and the
+// gate-weighted blend of Eq. 5.  All of them move 16-byte chunks of token rows (a 256-byte
+// bf16 row of head_dim 128 is one fully coalesced segment whatever order rows are visited in);
+// the index arithmetic is done once per row chunk and amortised over the heads of a route.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "vorta_internal.h"
+
+namespace vorta {
+
+#define VORTA_HIP(call)                                                                    \
+  do {                                                                                     \
+    hipError_t e_ = (call);                                                                \
+    if (e_ != hipSuccess) return fail(VORTA_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+static int launch_status(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(VORTA_EHIP, "launch of %s: %s", what, hipGetErrorString(e));
+  return VORTA_OK;
+}
+
+int ensure_device_tables(vorta_plan* p) {
+  std::lock_guard<std::mutex> lock(p->mu);
+  if (p->on_device) return VORTA_OK;
+  int dev = -1;
+  VORTA_HIP(hipGetDevice(&dev));
+  VORTA_HIP(hipMalloc(&p->d_runs, p->runs.size() * sizeof(int32_t)));
+  VORTA_HIP(hipMalloc(&p->d_n_runs, p->n_runs.size() * sizeof(int32_t)));
+  VORTA_HIP(hipMalloc(&p->d_slot_base, p->slot_base.size() * sizeof(int32_t)));
+  VORTA_HIP(hipMemcpy(p->d_runs, p->runs.data(), p->runs.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+  VORTA_HIP(hipMemcpy(p->d_n_runs, p->n_runs.data(), p->n_runs.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+  VORTA_HIP(hipMemcpy(p->d_slot_base, p->slot_base.data(), p->slot_base.size() * sizeof(int32_t),
+                      hipMemcpyHostToDevice));
+  p->device = dev;
+  p->on_device = true;
+  return VORTA_OK;
+}
+
+struct HeadList {
+  int n;
+  uint8_t id[VORTA_MAX_HEADS];
+};
+
+static HeadList head_list(const RouteLists& rl, int route) {
+  HeadList h;
+  h.n = rl.count[route];
+  for (int i = 0; i < h.n; ++i) h.id[i] = (uint8_t)rl.heads[route][i];
+  return h;
+}
+
+struct Geo {
+  int F, H, W;
+  int tF, tH, tW;
+  int nH, nW;       // tile grid along H, W
+  int tile_tokens;
+  int L, N;
+  int bF, bH, bW;   // bucket
+  int nbH, nbW;     // bucket grid along H, W
+  int keep_num, keep_den;
+};
+
+static Geo make_geo(const vorta_plan* p) {
+  Geo g;
+  g.F = p->d.F; g.H = p->d.H; g.W = p->d.W;
+  g.tF = p->d.tile[0]; g.tH = p->d.tile[1]; g.tW = p->d.tile[2];
+  g.nH = p->nt[1]; g.nW = p->nt[2];
+  g.tile_tokens = p->tile_tokens;
+  g.L = (int)p->L; g.N = (int)p->N;
+  g.bF = p->d.bucket[0]; g.bH = p->d.bucket[1]; g.bW = p->d.bucket[2];
+  g.nbH = p->nb[1]; g.nbW = p->nb[2];
+  g.keep_num = p->d.keep_num; g.keep_den = p->d.keep_den;
+  return g;
+}
+
+// Position in tile order -> frame-major raster index (inverse of get_tile_id_3d + local id).
+__device__ __forceinline__ int tiled_to_raster(const Geo& g, int pos) {
+  const int tile = pos / g.tile_tokens, local = pos - tile * g.tile_tokens;
+  const int tiles_hw = g.nH * g.nW;
+  const int tf = tile / tiles_hw, tr = tile - tf * tiles_hw;
+  const int th = tr / g.nW, tw = tr - th * g.nW;
+  const int loc_hw = g.tH * g.tW;
+  const int lf = local / loc_hw, lr = local - lf * loc_hw;
+  const int lh = lr / g.tW, lw = lr - lh * g.tW;
+  return ((tf * g.tF + lf) * g.H + th * g.tH + lh) * g.W + tw * g.tW + lw;
+}
+
+// ------------------------------------------------------------------------------------------
+// reorder: one thread per (tile-order row, 16-byte chunk), looping over the heads of route 1
+// ------------------------------------------------------------------------------------------
+template <bool TO_TILES>
+__global__ __launch_bounds__(256) void reorder_kernel(uint4* __restrict__ user, uint4* __restrict__ tiled,
+                                                      HeadList hl, Geo g, long head_stride_c,
+                                                      long row_stride_c, int cshift) {
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const int pos = (int)(gid >> cshift);
+  const int c = (int)(gid & ((1 << cshift) - 1));
+  if (pos >= g.N) return;
+  const int i = pos < g.L ? tiled_to_raster(g, pos) : pos;   // text rows keep their place
+  const long u0 = (long)i * row_stride_c + c;
+  const long t0 = ((long)pos << cshift) + c;
+  const long tiled_head = (long)g.N << cshift;
+#pragma unroll 4
+  for (int s = 0; s < hl.n; ++s) {
+    const long u = u0 + hl.id[s] * head_stride_c, t = t0 + s * tiled_head;
+    if (TO_TILES) tiled[t] = user[u];
+    else user[u] = tiled[t];
+  }
+}
+
+static int chunk_shift(const vorta_plan* p) {
+  const int chunks = p->d.head_dim * p->elem_bytes / 16;   // 16 or 32
+  return chunks == 32 ? 5 : 4;
+}
+
+int launch_reorder(vorta_plan* p, const RouteLists& rl, const void* user, void* tiled, bool to_tiles,
+                   void* stream) {
+  if (rl.count[1] == 0) return VORTA_OK;
+  const UserTensor ut = user_tensor(p, user);
+  const int cs = chunk_shift(p);
+  const int epc = 16 / p->elem_bytes;   // elements per chunk
+  const long total = (long)p->N << cs;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  const HeadList hl = head_list(rl, 1);
+  const Geo g = make_geo(p);
+  hipStream_t st = (hipStream_t)stream;
+  if (to_tiles)
+    hipLaunchKernelGGL(reorder_kernel<true>, dim3(blocks), dim3(256), 0, st, (uint4*)user, (uint4*)tiled, hl, g,
+                       ut.head_stride / epc, ut.row_stride / epc, cs);
+  else
+    hipLaunchKernelGGL(reorder_kernel<false>, dim3(blocks), dim3(256), 0, st, (uint4*)user, (uint4*)tiled, hl,
+                       g, ut.head_stride / epc, ut.row_stride / epc, cs);
+  return launch_status("reorder_kernel");
+}
+
+// ------------------------------------------------------------------------------------------
+// unpool: out[i] = o_c[assign[i]] for the heads of route 2 (text rows: o_c[L_c + t])
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void unpool_kernel(uint4* __restrict__ out, const uint4* __restrict__ o_c,
+                                                     const int* __restrict__ assign, HeadList hl, int L,
+                                                     int N, int Lc, long head_stride_c, long row_stride_c,
+                                                     int cshift) {
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const int i = (int)(gid >> cshift);
+  const int c = (int)(gid & ((1 << cshift) - 1));
+  if (i >= N) return;
+  const long u0 = (long)i * row_stride_c + c;
+  const long core_head = (long)(Lc + N - L) << cshift;
+#pragma unroll 4
+  for (int s = 0; s < hl.n; ++s) {
+    const int slot = i < L ? assign[(long)s * L + i] : Lc + (i - L);
+    out[u0 + hl.id[s] * head_stride_c] = o_c[s * core_head + ((long)slot << cshift) + c];
+  }
+}
+
+int launch_unpool(vorta_plan* p, const RouteLists& rl, const void* o_c, const int32_t* assign, void* out,
+                  void* stream) {
+  if (rl.count[2] == 0) return VORTA_OK;
+  const UserTensor ut = user_tensor(p, out);
+  const int cs = chunk_shift(p);
+  const int epc = 16 / p->elem_bytes;
+  const long total = (long)p->N << cs;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  hipLaunchKernelGGL(unpool_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)out,
+                     (const uint4*)o_c, assign, head_list(rl, 2), (int)p->L, (int)p->N, (int)p->Lc,
+                     ut.head_stride / epc, ut.row_stride / epc, cs);
+  return launch_status("unpool_kernel");
+}
+
+// ------------------------------------------------------------------------------------------
+// Bucketed core-set selection.  One wavefront per (bucket, head): lanes split the feature
+// dimension, fp64 dot products are reduced across the wavefront, then lane j ranks token j.
+// ------------------------------------------------------------------------------------------
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  __device__ static double load(const float* p) { return (double)*p; }
+  __device__ static void store(float* p, double v) { *p = (float)v; }
+};
+template <> struct Elem<uint16_t> {   // bf16 bits
+  __device__ static double load(const uint16_t* p) { return (double)__uint_as_float((unsigned)*p << 16); }
+  __device__ static void store(uint16_t* p, double v) {
+    const unsigned u = __float_as_uint((float)v);      // round-to-nearest-even on the upper 16 bits
+    *p = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+  }
+};
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+struct Bucket {
+  int f0, h0, w0;   // origin
+  int df, dh, dw;   // clipped extent
+  int size, centre, prune;
+};
+
+__device__ __forceinline__ Bucket bucket_of(const Geo& g, int b) {
+  Bucket k;
+  const int per_f = g.nbH * g.nbW;
+  const int bf = b / per_f, r = b - bf * per_f;
+  const int bh = r / g.nbW, bw = r - bh * g.nbW;
+  k.f0 = bf * g.bF; k.h0 = bh * g.bH; k.w0 = bw * g.bW;
+  k.df = min(g.bF, g.F - k.f0); k.dh = min(g.bH, g.H - k.h0); k.dw = min(g.bW, g.W - k.w0);
+  k.size = k.df * k.dh * k.dw;
+  k.centre = ((k.df / 2) * k.dh + k.dh / 2) * k.dw + k.dw / 2;
+  k.prune = min(k.size - 1, (int)(((long)k.size * (g.keep_den - g.keep_num)) / g.keep_den));
+  return k;
+}
+
+__device__ __forceinline__ int bucket_token(const Geo& g, const Bucket& k, int j) {
+  const int hw = k.dh * k.dw;
+  const int a = j / hw, r = j - a * hw;
+  const int b = r / k.dw, c = r - b * k.dw;
+  return ((k.f0 + a) * g.H + k.h0 + b) * g.W + k.w0 + c;
+}
+
+template <typename T, int DPL>   // DPL = head_dim / 64 feature elements per lane
+__global__ __launch_bounds__(256) void bcs_index_kernel(const T* __restrict__ feat, HeadList hl, Geo g,
+                                                        int n_buckets, const int* __restrict__ slot_base,
+                                                        long head_stride, long row_stride, int Lc,
+                                                        int* __restrict__ keep_idx, int* __restrict__ assign) {
+#pragma clang fp contract(off)
+  const int lane = threadIdx.x & 63;
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int s = blockIdx.y;
+  if (b >= n_buckets) return;
+  const Bucket k = bucket_of(g, b);
+  const T* base = feat + hl.id[s] * head_stride + lane * DPL;
+
+  double xc[DPL], nc = 0.0;
+  {
+    const T* row = base + (long)bucket_token(g, k, k.centre) * row_stride;
+#pragma unroll
+    for (int e = 0; e < DPL; ++e) { xc[e] = Elem<T>::load(row + e); nc += xc[e] * xc[e]; }
+  }
+  nc = wave_sum(nc);
+
+  double my_sim = 0.0;
+  for (int j = 0; j < k.size; ++j) {
+    if (j == k.centre) continue;
+    const T* row = base + (long)bucket_token(g, k, j) * row_stride;
+    double dot = 0.0, nj = 0.0;
+#pragma unroll
+    for (int e = 0; e < DPL; ++e) {
+      const double x = Elem<T>::load(row + e);
+      dot += xc[e] * x;
+      nj += x * x;
+    }
+    dot = wave_sum(dot);
+    nj = wave_sum(nj);
+    double sim = 0.0;
+    if (nc != 0.0 && nj != 0.0) sim = dot / sqrt(nc * nj);
+    if (!(sim == sim)) sim = 0.0;       // non-finite features: keep the ranking a total order
+    if (lane == j) my_sim = sim;
+  }
+
+  // rank of token `lane` among the non-centre tokens: larger similarity first, ties by index
+  int rank = 0;
+  for (int m = 0; m < k.size; ++m) {
+    const double sm = __shfl(my_sim, m, 64);
+    if (m != k.centre && (sm > my_sim || (sm == my_sim && m < lane))) ++rank;
+  }
+  const bool in_bucket = lane < k.size;
+  const bool kept = in_bucket && (lane == k.centre || rank >= k.prune);
+  const unsigned long long kept_mask = __ballot(kept);
+  const int base_slot = slot_base[b];
+  const int my_slot = base_slot + __popcll(kept_mask & ((1ull << lane) - 1ull));
+  const int centre_slot = base_slot + __popcll(kept_mask & ((1ull << k.centre) - 1ull));
+  if (in_bucket) {
+    const int tok = bucket_token(g, k, lane);
+    if (kept) keep_idx[(long)s * Lc + my_slot] = tok;
+    assign[(long)s * g.L + tok] = kept ? my_slot : centre_slot;
+  }
+}
+
+int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const void* feat, int32_t* keep_idx,
+                     int32_t* assign, void* stream) {
+  if (rl.count[2] == 0) return VORTA_OK;
+  const UserTensor ut = user_tensor(p, feat);
+  const dim3 grid((p->n_buckets + 3) / 4, rl.count[2]);
+  const HeadList hl = head_list(rl, 2);
+  const Geo g = make_geo(p);
+  hipStream_t st = (hipStream_t)stream;
+  if (p->d.dtype == VORTA_BF16)
+    hipLaunchKernelGGL((bcs_index_kernel<uint16_t, 2>), grid, dim3(256), 0, st, (const uint16_t*)feat, hl, g,
+                       p->n_buckets, p->d_slot_base, ut.head_stride, ut.row_stride, (int)p->Lc, keep_idx, assign);
+  else if (p->d.head_dim == 64)
+    hipLaunchKernelGGL((bcs_index_kernel<float, 1>), grid, dim3(256), 0, st, (const float*)feat, hl, g,
+                       p->n_buckets, p->d_slot_base, ut.head_stride, ut.row_stride, (int)p->Lc, keep_idx, assign);
+  else
+    hipLaunchKernelGGL((bcs_index_kernel<float, 2>), grid, dim3(256), 0, st, (const float*)feat, hl, g,
+                       p->n_buckets, p->d_slot_base, ut.head_stride, ut.row_stride, (int)p->Lc, keep_idx, assign);
+  return launch_status("bcs_index_kernel");
+}
+
+// ------------------------------------------------------------------------------------------
+// pool / merge: one wavefront per (bucket, head); a kept token's row is copied to its slot,
+// the centre's slot receives the mean of the centre and the tokens pruned into it.
+// ------------------------------------------------------------------------------------------
+template <typename T, int DPL>
+__global__ __launch_bounds__(256) void bcs_pool_kernel(const T* __restrict__ src, HeadList hl, Geo g,
+                                                       int n_buckets, long head_stride, long row_stride,
+                                                       int Lc, int n_core_rows, int head_dim,
+                                                       const int* __restrict__ assign, T* __restrict__ dst) {
+  const int lane = threadIdx.x & 63;
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int s = blockIdx.y;
+  if (b >= n_buckets) return;
+  const Bucket k = bucket_of(g, b);
+  const T* base = src + hl.id[s] * head_stride + lane * DPL;
+  T* out = dst + (long)s * n_core_rows * head_dim + lane * DPL;
+
+  int my_slot = 0;
+  if (lane < k.size) my_slot = assign[(long)s * g.L + bucket_token(g, k, lane)];
+  const int centre_slot = __shfl(my_slot, k.centre, 64);
+  double acc[DPL];
+#pragma unroll
+  for (int e = 0; e < DPL; ++e) acc[e] = 0.0;
+  int members = 0;
+  for (int j = 0; j < k.size; ++j) {
+    const int slot = __shfl(my_slot, j, 64);
+    const T* row = base + (long)bucket_token(g, k, j) * row_stride;
+    if (slot == centre_slot) {
+#pragma unroll
+      for (int e = 0; e < DPL; ++e) acc[e] += Elem<T>::load(row + e);
+      ++members;
+    } else {
+#pragma unroll
+      for (int e = 0; e < DPL; ++e) out[(long)slot * head_dim + e] = row[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < DPL; ++e) Elem<T>::store(out + (long)centre_slot * head_dim + e, acc[e] / (double)members);
+}
+
+// text rows ride along unchanged behind the L_c pooled rows
+__global__ __launch_bounds__(256) void copy_text_rows_kernel(const uint4* __restrict__ user,
+                                                             uint4* __restrict__ core, HeadList hl, int L,
+                                                             int n_text, int Lc, long head_stride_c,
+                                                             long row_stride_c, int cshift) {
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const int t = (int)(gid >> cshift);
+  const int c = (int)(gid & ((1 << cshift) - 1));
+  if (t >= n_text) return;
+  const long core_head = (long)(Lc + n_text) << cshift;
+  for (int s = 0; s < hl.n; ++s)
+    core[s * core_head + ((long)(Lc + t) << cshift) + c] =
+        user[hl.id[s] * head_stride_c + (long)(L + t) * row_stride_c + c];
+}
+
+int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const int32_t* keep_idx,
+                    const int32_t* assign, void* dst, void* stream) {
+  (void)keep_idx;   // the slot of every token is in `assign`; kept for a symmetric interface
+  if (rl.count[2] == 0) return VORTA_OK;
+  const UserTensor ut = user_tensor(p, src);
+  const dim3 grid((p->n_buckets + 3) / 4, rl.count[2]);
+  const HeadList hl = head_list(rl, 2);
+  const Geo g = make_geo(p);
+  const int rows = (int)(p->Lc + p->d.n_text);
+  hipStream_t st = (hipStream_t)stream;
+  if (p->d.dtype == VORTA_BF16)
+    hipLaunchKernelGGL((bcs_pool_kernel<uint16_t, 2>), grid, dim3(256), 0, st, (const uint16_t*)src, hl, g,
+                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, p->d.head_dim, assign,
+                       (uint16_t*)dst);
+  else if (p->d.head_dim == 64)
+    hipLaunchKernelGGL((bcs_pool_kernel<float, 1>), grid, dim3(256), 0, st, (const float*)src, hl, g,
+                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, p->d.head_dim, assign,
+                       (float*)dst);
+  else
+    hipLaunchKernelGGL((bcs_pool_kernel<float, 2>), grid, dim3(256), 0, st, (const float*)src, hl, g,
+                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, p->d.head_dim, assign,
+                       (float*)dst);
+  if (int rc = launch_status("bcs_pool_kernel")) return rc;
+  if (p->d.n_text > 0) {
+    const int cs = chunk_shift(p);
+    const int epc = 16 / p->elem_bytes;
+    const long total = (long)p->d.n_text << cs;
+    hipLaunchKernelGGL(copy_text_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const uint4*)src, (uint4*)dst, hl, (int)p->L, p->d.n_text, (int)p->Lc,
+                       ut.head_stride / epc, ut.row_stride / epc, cs);
+    return launch_status("copy_text_rows_kernel");
+  }
+  return VORTA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 5 blend: out = a1 o_full + a2 o_sliding + a3 o_coreset, gates per head
+// ------------------------------------------------------------------------------------------
+struct Gates {
+  float a[VORTA_MAX_HEADS][3];
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void blend_kernel(const T* __restrict__ o0, const T* __restrict__ o1,
+                                                    const T* __restrict__ o2, T* __restrict__ out, Gates gt,
+                                                    long total, int head_dim, int heads, long N, int layout) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const long row = i / head_dim;
+  const int h = layout == VORTA_LAYOUT_NHD ? (int)(row % heads) : (int)(row / N);
+  const double v = (double)gt.a[h][0] * Elem<T>::load(o0 + i) + (double)gt.a[h][1] * Elem<T>::load(o1 + i) +
+                   (double)gt.a[h][2] * Elem<T>::load(o2 + i);
+  Elem<T>::store(out + i, v);
+}
+
+int launch_blend3(vorta_plan* p, const void* o0, const void* o1, const void* o2, const float* alpha_host,
+                  void* out, void* stream) {
+  Gates gt;
+  std::memset(&gt, 0, sizeof(gt));
+  for (int h = 0; h < p->d.heads; ++h)
+    for (int r = 0; r < 3; ++r) gt.a[h][r] = alpha_host[3 * h + r];
+  const long total = (long)p->d.heads * p->N * p->d.head_dim;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  hipStream_t st = (hipStream_t)stream;
+  if (p->d.dtype == VORTA_BF16)
+    hipLaunchKernelGGL(blend_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)o0,
+                       (const uint16_t*)o1, (const uint16_t*)o2, (uint16_t*)out, gt, total, p->d.head_dim,
+                       p->d.heads, (long)p->N, p->d.layout);
+  else
+    hipLaunchKernelGGL(blend_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)o0, (const float*)o1,
+                       (const float*)o2, (float*)out, gt, total, p->d.head_dim, p->d.heads, (long)p->N,
+                       p->d.layout);
+  return launch_status("blend_kernel");
+}
+
+}  // namespace vorta
+
+extern "C" int vorta_plan_destroy(vorta_plan* p) {
+  vorta::clear_error();
+  if (!p) return VORTA_OK;
+  if (p->on_device) {
+    (void)hipFree(p->d_runs);
+    (void)hipFree(p->d_n_runs);
+    (void)hipFree(p->d_slot_base);
+  }
+  delete p;
+  return VORTA_OK;
+}

@@ -1,0 +1,281 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same
+seeded inputs.  Index sets, routes and permutations bit-exact; outputs within max-abs
+1e-5 (fp32) and 2e-2 (bf16, unit-variance inputs)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_18809_amd as vorta
+from oracle import vorta_oracle as vo
+from synth_inputs import LayerConfig, get_config, make_qkv, make_routes
+from helpers import f64, spec_of
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-5, "bf16": 2e-2}
+DEV = "cuda"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    return torch.from_numpy(np.asarray(x, dtype=np.float64)).to(torch.bfloat16).double().numpy()
+
+
+def small_cfg(name, grid, heads, dtype, tile, window, routes, d=128, n_text=0, seed=11, **kw):
+    return LayerConfig(name, grid, heads, d, dtype, tile, window, seed=seed, n_text=n_text,
+                       fixed_routes=tuple(routes), **kw)
+
+
+def run_layer(cfg, q, k, v, routes, layout=1, **plan_over):
+    plan = vorta.plan_for(cfg, layout=layout, **plan_over)
+    out = vorta.vorta_routed_attention_layer(plan, q, k, v, routes)
+    torch.cuda.synchronize()
+    return plan, out
+
+
+def hnd(t, layout):
+    return t if layout == 1 else t.transpose(0, 1)
+
+
+# ------------------------------------------------------------------ memory passes --------
+
+@pytest.mark.parametrize("layout", [1, 0])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64), ("fp32", 128)])
+def test_reorder_to_tiles_and_back_is_the_tile_permutation(dtype, d, layout):
+    cfg = small_cfg("reorder", (4, 6, 8), 5, dtype, (2, 3, 4), (3, 3, 3), [1, 0, 1, 2, 1], d=d, n_text=7)
+    say(f"reorder {dtype} d={d} layout={layout}")
+    q, _, _ = make_qkv(cfg, DEV, layout)
+    plan = vorta.plan_for(cfg, layout=layout)
+    routes = np.array(cfg.fixed_routes, dtype=np.uint8)
+    tiled = vorta.vorta_reorder_to_tiles(plan, q, routes)
+    torch.cuda.synchronize()
+    perm = torch.from_numpy(vorta.vorta_tile_permutation(plan).astype(np.int64)).to(DEV)
+    L = cfg.n_video
+    src = hnd(q, layout)
+    for slot, h in enumerate([0, 2, 4]):
+        want = torch.empty_like(src[h])
+        want[perm] = src[h][:L]
+        want[L:] = src[h][L:]
+        assert torch.equal(tiled[slot], want), (slot, h)
+    back = torch.full_like(q, 7.0)
+    vorta.vorta_reorder_from_tiles(plan, tiled, routes, back)
+    torch.cuda.synchronize()
+    b = hnd(back, layout)
+    for h in range(5):
+        if routes[h] == 1:
+            assert torch.equal(b[h], src[h])
+        else:
+            assert (b[h] == 7.0).all()          # other heads' rows are not touched
+
+
+@pytest.mark.parametrize("name,grid,bucket,num,den,dtype,d", [
+    ("even", (4, 6, 8), (2, 3, 2), 1, 2, "bf16", 128),
+    ("ragged", (5, 7, 9), (2, 3, 2), 1, 2, "bf16", 128),
+    ("quarter", (4, 8, 8), (2, 2, 4), 1, 4, "bf16", 128),
+    ("keepall", (3, 4, 5), (2, 3, 2), 1, 1, "bf16", 128),
+    ("fp32", (4, 8, 8), (2, 3, 2), 1, 2, "fp32", 64),
+    ("fp32d128", (3, 5, 4), (3, 2, 2), 2, 3, "fp32", 128),
+])
+def test_bcs_index_pool_and_unpool_match_oracle(name, grid, bucket, num, den, dtype, d):
+    cfg = small_cfg(name, grid, 3, dtype, (1, 1, 1), (1, 1, 1), [2, 0, 2], d=d, n_text=3, bucket=bucket,
+                    keep_num=num, keep_den=den)
+    say(f"bcs {name}")
+    q, k, v = make_qkv(cfg, DEV)
+    plan = vorta.plan_for(cfg)
+    routes = np.array(cfg.fixed_routes, dtype=np.uint8)
+    keep_idx, assign = vorta.vorta_bcs_build_index(plan, k, routes)
+    pooled = vorta.vorta_bcs_pool(plan, v, routes, keep_idx, assign)
+    torch.cuda.synchronize()
+    L = cfg.n_video
+    for slot, h in enumerate([0, 2]):
+        ki, asg, gap = vo.bcs_select(f64(k[h])[:L], grid, bucket, num, den)
+        assert gap > 1e-9, "tie-proof input expected"
+        assert np.array_equal(keep_idx[slot].cpu().numpy(), ki)
+        assert np.array_equal(assign[slot].cpu().numpy(), asg)
+        want = np.concatenate([vo.bcs_pool(f64(v[h])[:L], ki, asg), f64(v[h])[L:]])
+        got = f64(pooled[slot])
+        if dtype == "bf16":
+            assert np.abs(got - want).max() <= 2.0 ** -8 * max(1.0, np.abs(want).max())
+            single = np.bincount(asg, minlength=len(ki)) == 1
+            assert np.array_equal(got[:len(ki)][single], want[:len(ki)][single])     # kept rows are copies
+        else:
+            assert np.abs(got - want).max() < 1e-6
+    # unpool: every token reads its slot, text rows their own
+    o_c = torch.randn(2, plan.n_core_tokens, d, device=DEV).to(q.dtype)
+    out = torch.zeros_like(q)
+    vorta.vorta_scatter_back(plan, routes, None, o_c, assign, out)
+    torch.cuda.synchronize()
+    for slot, h in enumerate([0, 2]):
+        src = torch.cat([assign[slot].long(), plan.n_core + torch.arange(3, device=DEV)])
+        assert torch.equal(out[h], o_c[slot][src])
+    assert (out[1] == 0).all()
+
+
+# ------------------------------------------------------------------ whole layer ----------
+
+def check_layer(cfg, routes, layout=1, rows=None, **plan_over):
+    q, k, v = make_qkv(cfg, DEV, layout)
+    plan, out = run_layer(cfg, q, k, v, routes, layout, **plan_over)
+    over = {}
+    if "center_mode" in plan_over:
+        over["center_mode"] = "identity" if plan_over["center_mode"] else "clamp"
+    spec = spec_of(cfg, **over)
+    qh, kh, vh, oh = (hnd(t, layout) for t in (q, k, v, out))
+    worst = 0.0
+    for h, r in enumerate(routes):
+        want = vo.head_attention(int(r), f64(qh[h]), f64(kh[h]), f64(vh[h]), spec, rows)
+        got = f64(oh[h]) if rows is None else f64(oh[h][torch.as_tensor(rows, device=DEV)])
+        err = np.abs(got - want).max()
+        worst = max(worst, err)
+        assert err <= TOL[cfg.dtype], f"{cfg.name} head {h} route {r}: max-abs {err:.3e}"
+    say(f"{cfg.name} layout={layout} routes={list(map(int, routes))}: max-abs {worst:.3e}")
+    return plan, out
+
+
+@pytest.mark.parametrize("route", [0, 1, 2])
+def test_tiny_config_every_head_under_every_route(route):
+    cfg = get_config("tiny")
+    check_layer(cfg, [route] * cfg.heads)
+
+
+@pytest.mark.parametrize("layout", [1, 0])
+def test_single_layer_config(layout):
+    cfg = get_config("single")
+    check_layer(cfg, make_routes(cfg).numpy(), layout)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64), ("fp32", 128)])
+def test_ragged_shapes_text_tokens_and_mixed_routes(dtype, d):
+    # N = 5*6*9 + 37 = 307: not a multiple of any block size; 90-token tiles; clipped buckets
+    cfg = small_cfg("ragged", (5, 6, 9), 4, dtype, (5, 2, 3), (1, 3, 3), [2, 1, 0, 1], d=d, n_text=37)
+    check_layer(cfg, cfg.fixed_routes)
+    check_layer(cfg, cfg.fixed_routes, layout=0)
+
+
+def test_window_identity_centres_and_wide_windows():
+    cfg = small_cfg("ident", (4, 8, 8), 2, "bf16", (2, 2, 2), (1, 3, 5), [1, 1])
+    check_layer(cfg, cfg.fixed_routes, center_mode=1)
+    check_layer(cfg, cfg.fixed_routes, center_mode=0)
+
+
+def test_degenerate_cases():
+    # one tile, one bucket row, window of one tile, core-set keeping everything
+    cfg = small_cfg("one_tile", (1, 2, 3), 3, "bf16", (1, 2, 3), (1, 1, 1), [0, 1, 2])
+    check_layer(cfg, cfg.fixed_routes)
+    keep = small_cfg("keep_all", (2, 3, 4), 2, "fp32", (1, 1, 1), (1, 1, 1), [2, 0], d=64, keep_num=1, keep_den=1)
+    plan, out = check_layer(keep, keep.fixed_routes)
+    # no head on some routes; empty route groups must be no-ops
+    only_full = small_cfg("only_full", (2, 4, 4), 2, "bf16", (1, 2, 2), (3, 3, 3), [0, 0])
+    check_layer(only_full, only_full.fixed_routes)
+    # tile larger than a query block: several q-blocks per tile
+    big_tile = small_cfg("big_tile", (4, 8, 10), 1, "bf16", (4, 8, 5), (1, 1, 1), [1])
+    check_layer(big_tile, big_tile.fixed_routes)
+
+
+def test_layer_equals_the_staged_calls_and_is_deterministic():
+    cfg = get_config("single")
+    routes = make_routes(cfg).numpy()
+    q, k, v = make_qkv(cfg, DEV)
+    plan, out = run_layer(cfg, q, k, v, routes)
+    out2 = vorta.vorta_routed_attention_layer(plan, q, k, v, routes)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    q_t, k_t, v_t = (vorta.vorta_reorder_to_tiles(plan, t, routes) for t in (q, k, v))
+    keep_idx, assign = vorta.vorta_bcs_build_index(plan, k, routes)
+    q_c, k_c, v_c = (vorta.vorta_bcs_pool(plan, t, routes, keep_idx, assign) for t in (q, k, v))
+    o_t, o_c, staged = torch.empty_like(q_t), torch.empty_like(q_c), torch.zeros_like(q)
+    vorta.vorta_attention_routed(plan, routes, q=q, k=k, v=v, out=staged, q_t=q_t, k_t=k_t, v_t=v_t, o_t=o_t,
+                                 q_c=q_c, k_c=k_c, v_c=v_c, o_c=o_c)
+    vorta.vorta_scatter_back(plan, routes, o_t, o_c, assign, staged)
+    torch.cuda.synchronize()
+    assert torch.equal(out, staged)
+
+
+def test_soft_mixture_blends_the_three_branches():
+    cfg = small_cfg("mix", (4, 4, 6), 3, "bf16", (2, 2, 3), (1, 3, 1), [0, 1, 2])
+    q, k, v = make_qkv(cfg, DEV)
+    plan = vorta.plan_for(cfg)
+    alpha = np.array([[0.2, 0.5, 0.3], [1.0, 0.0, 0.0], [0.1, 0.1, 0.8]])
+    out = vorta.vorta_soft_mixture_layer(plan, q, k, v, alpha)
+    torch.cuda.synchronize()
+    want = vo.soft_mixture_layer(f64(q), f64(k), f64(v), alpha, spec_of(cfg))
+    err = np.abs(f64(out) - want).max()
+    say(f"soft mixture max-abs {err:.3e}")
+    assert err <= 2e-2
+
+
+def test_error_paths_do_not_launch():
+    cfg = get_config("tiny")
+    q, k, v = make_qkv(cfg, DEV)
+    plan = vorta.plan_for(cfg)
+    with pytest.raises(vorta.VortaError) as e:
+        vorta.vorta_routed_attention_layer(plan, q, k, v, [0, 5])
+    assert e.value.code == -5
+    with pytest.raises(vorta.VortaError) as e:
+        vorta.vorta_routed_attention_layer(plan, q, k, v, [1, 2], workspace=torch.empty(512, dtype=torch.uint8, device=DEV))
+    assert e.value.code == -4
+    with pytest.raises(vorta.VortaError) as e:
+        vorta.vorta_routed_attention_layer(plan, q.view(-1)[1:-3].view(-1), k, v, [0, 0])
+    assert e.value.code == -7
+
+
+# ------------------------------------------------------------------ full-size layers -----
+
+def sampled_rows(cfg, plan, head, rng):
+    """Rows the oracle evaluates one by one: seeded random rows, every row of a corner tile
+    and of an interior tile, the last rows, and all text rows."""
+    L = cfg.n_video
+    perm = vorta.vorta_tile_permutation(plan)
+    tt = plan.tile_tokens
+    corner = np.nonzero(perm // tt == 0)[0]
+    mid = np.nonzero(perm // tt == plan.n_tiles // 2 + plan.tiles[2] // 2)[0]
+    rows = np.concatenate([rng.choice(L, 24, replace=False), corner[:: max(1, len(corner) // 16)],
+                           mid[:: max(1, len(mid) // 16)], np.arange(L - 3, L),
+                           L + np.arange(0, cfg.n_text, 16)])
+    return np.unique(rows)
+
+
+@pytest.mark.parametrize("name", ["wan480p", "wan720p", "hunyuan720p"])
+def test_full_size_layer_on_sampled_rows(name):
+    cfg = get_config(name)
+    routes = make_routes(cfg).numpy()
+    say(f"{name}: generating inputs")
+    q, k, v = make_qkv(cfg, DEV)
+    plan = vorta.plan_for(cfg)
+    ws = torch.empty(vorta.vorta_workspace_bytes(plan, routes), dtype=torch.uint8, device=DEV)
+    out = vorta.vorta_routed_attention_layer(plan, q, k, v, routes, workspace=ws)
+    torch.cuda.synchronize()
+    say(f"{name}: layer done, checking against the oracle")
+    off = vorta.vorta_workspace_layout(plan, routes)
+    n_lr = int((routes == 2).sum())
+    keep_idx = ws[off[8]: off[8] + n_lr * plan.n_core * 4].view(torch.int32).view(n_lr, plan.n_core).cpu().numpy()
+    assign = ws[off[9]: off[9] + n_lr * plan.n_video * 4].view(torch.int32).view(n_lr, plan.n_video).cpu().numpy()
+    spec = spec_of(cfg)
+    rng = np.random.default_rng(cfg.seed)
+    worst = [0.0, 0.0, 0.0]
+    lr_slot = 0
+    L = cfg.n_video
+    for h, r in enumerate(routes):
+        rows = sampled_rows(cfg, plan, h, rng)
+        Q, K, V = f64(q[h]), f64(k[h]), f64(v[h])
+        if r == 2:
+            ki, asg, gap = vo.bcs_select(K[:L], cfg.grid, cfg.bucket, cfg.keep_num, cfg.keep_den)
+            assert gap > 1e-12
+            assert np.array_equal(keep_idx[lr_slot], ki) and np.array_equal(assign[lr_slot], asg), f"head {h}"
+            lr_slot += 1
+            want = vo.coreset_attention(Q, K, V, spec, rows, index=(ki, asg))
+        else:
+            want = vo.head_attention(int(r), Q, K, V, spec, rows)
+        got = f64(out[h][torch.as_tensor(rows, device=DEV)])
+        err = np.abs(got - want).max()
+        worst[r] = max(worst[r], err)
+        say(f"  {name} head {h:2d} route {r}: {len(rows)} rows, max-abs {err:.3e}")
+        assert err <= TOL[cfg.dtype], f"{name} head {h} route {r}: {err}"
+    assert torch.isfinite(out.float()).all()
+    say(f"{name}: worst max-abs per route {worst}")
