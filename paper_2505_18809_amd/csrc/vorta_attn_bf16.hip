@@ -47,6 +47,18 @@ __device__ __forceinline__ bf16x8 read_vt(const uint16_t* p_lo, const uint16_t* 
   return __builtin_bit_cast(bf16x8, both);
 }
 
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+__device__ __forceinline__ bf16x8 lds_frag(const uint16_t* p) {
+  return __builtin_bit_cast(bf16x8, *(const uint4*)p);
+}
+
+#define MFMA(a_, b_, c_) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b_, c_, 0, 0, 0)
+
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const WorkItem w = decode_item<BM, D>(a, blockIdx.x);
@@ -54,6 +66,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
   const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
   const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
   uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
+  const unsigned row_stride = (unsigned)w.row_stride;   // rows * stride < 2^31 elements (checked on the host)
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
@@ -61,49 +74,53 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
   // Q^T fragments: lane = query (l32), 8 consecutive dims per 16-wide k slice
   bf16x8 qf[8];
   {
-    const int qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
-    const uint16_t* qp = Q + (long)qrow * w.row_stride + 8 * g;
+    const unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    const uint16_t* qp = Q + qrow * row_stride + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * ks));
   }
 
   // global -> LDS staging: thread moves the 16-byte chunk (tid & 15) of rows (tid >> 4) + 16 i
   const int ld_row = tid >> 4, ld_col = (tid & 15) * 8;
-  uint4 kreg[4], vreg[4];
-  auto fetch = [&](int start, int len, int pos) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = min(pos + ld_row + 16 * i, len - 1);   // rows past the run repeat its last row
-      const long off = (long)(start + r) * w.row_stride + ld_col;
-      kreg[i] = *(const uint4*)(K + off);
-      vreg[i] = *(const uint4*)(V + off);
-    }
-  };
-  auto stage = [&](int buf) {
-    uint16_t* kb = smem + buf * 2 * TILE + ld_row * LSTR + ld_col;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *(uint4*)(kb + 16 * i * LSTR) = kreg[i];
-      *(uint4*)(kb + TILE + 16 * i * LSTR) = vreg[i];
-    }
-  };
+  uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
+#define FETCH_ROW(i_, kr_, vr_, start_, len_, pos_)                                        \
+  {                                                                                        \
+    const unsigned off_ = (unsigned)((start_) + min((pos_) + ld_row + 16 * (i_), (len_)-1)) * row_stride + ld_col; \
+    kr_ = *(const uint4*)(K + off_);                                                       \
+    vr_ = *(const uint4*)(V + off_);                                                       \
+  }
+#define FETCH(start_, len_, pos_)                  \
+  FETCH_ROW(0, kr0, vr0, start_, len_, pos_)       \
+  FETCH_ROW(1, kr1, vr1, start_, len_, pos_)       \
+  FETCH_ROW(2, kr2, vr2, start_, len_, pos_)       \
+  FETCH_ROW(3, kr3, vr3, start_, len_, pos_)
+#define STAGE(buf_)                                                       \
+  {                                                                       \
+    uint16_t* kb_ = smem + (buf_)*2 * TILE + ld_row * LSTR + ld_col;      \
+    *(uint4*)(kb_) = kr0;                                                 \
+    *(uint4*)(kb_ + 16 * LSTR) = kr1;                                     \
+    *(uint4*)(kb_ + 32 * LSTR) = kr2;                                     \
+    *(uint4*)(kb_ + 48 * LSTR) = kr3;                                     \
+    *(uint4*)(kb_ + TILE) = vr0;                                          \
+    *(uint4*)(kb_ + TILE + 16 * LSTR) = vr1;                              \
+    *(uint4*)(kb_ + TILE + 32 * LSTR) = vr2;                              \
+    *(uint4*)(kb_ + TILE + 48 * LSTR) = vr3;                              \
+  }
   auto run_start = [&](int r) { return w.runs ? w.runs[2 * r] : 0; };
   auto run_len = [&](int r) { return w.runs ? w.runs[2 * r + 1] : w.single_len; };
 
   int n_blocks = 0;
   for (int r = 0; r < w.n_runs; ++r) n_blocks += (run_len(r) + BN - 1) / BN;
 
-  f32x16 o[4];
+  f32x16 o0, o1, o2, o3;
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
+  for (int v = 0; v < 16; ++v) { o0[v] = 0.f; o1[v] = 0.f; o2[v] = 0.f; o3[v] = 0.f; }
   float m_run = -INFINITY, l_run = 0.f;
   const float c = a.scale * 1.4426950408889634f;
 
   int r = 0, pos = 0, start = run_start(0), len = run_len(0);
-  fetch(start, len, 0);
-  stage(0);
+  FETCH(start, len, 0)
+  STAGE(0)
   __syncthreads();
 
   // per-lane LDS read offsets
@@ -120,21 +137,33 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
       if (nr < w.n_runs) { nstart = run_start(nr); nlen = run_len(nr); }
     }
     const bool has_next = it + 1 < n_blocks;
-    if (has_next) fetch(nstart, nlen, npos);
+    if (has_next) { FETCH(nstart, nlen, npos) }
 
     const int n_valid = min(BN, len - pos);
-    const int buf_off = (it & 1) * 2 * TILE;
+    const uint16_t* kp = k_rd + (it & 1) * 2 * TILE;
+    const uint16_t* vp = v_rd + (it & 1) * 2 * TILE;
 
     // ---- S^T = K Q^T for keys [0,32) and [32,64) of the block
     f32x16 s0, s1;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { s0[v] = 0.f; s1[v] = 0.f; }
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const bf16x8 a0 = __builtin_bit_cast(bf16x8, *(const uint4*)(k_rd + buf_off + 16 * ks));
-      const bf16x8 a1 = __builtin_bit_cast(bf16x8, *(const uint4*)(k_rd + buf_off + 32 * LSTR + 16 * ks));
-      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s1, 0, 0, 0);
+    {
+      bf16x8 f0 = lds_frag(kp), f1 = lds_frag(kp + 32 * LSTR);
+      bf16x8 f2 = lds_frag(kp + 16), f3 = lds_frag(kp + 32 * LSTR + 16);
+      bf16x8 f4 = lds_frag(kp + 32), f5 = lds_frag(kp + 32 * LSTR + 32);
+      bf16x8 f6 = lds_frag(kp + 48), f7 = lds_frag(kp + 32 * LSTR + 48);
+      s0 = MFMA(f0, qf[0], s0); s1 = MFMA(f1, qf[0], s1);
+      f0 = lds_frag(kp + 64); f1 = lds_frag(kp + 32 * LSTR + 64);
+      s0 = MFMA(f2, qf[1], s0); s1 = MFMA(f3, qf[1], s1);
+      f2 = lds_frag(kp + 80); f3 = lds_frag(kp + 32 * LSTR + 80);
+      s0 = MFMA(f4, qf[2], s0); s1 = MFMA(f5, qf[2], s1);
+      f4 = lds_frag(kp + 96); f5 = lds_frag(kp + 32 * LSTR + 96);
+      s0 = MFMA(f6, qf[3], s0); s1 = MFMA(f7, qf[3], s1);
+      f6 = lds_frag(kp + 112); f7 = lds_frag(kp + 32 * LSTR + 112);
+      s0 = MFMA(f0, qf[4], s0); s1 = MFMA(f1, qf[4], s1);
+      s0 = MFMA(f2, qf[5], s0); s1 = MFMA(f3, qf[5], s1);
+      s0 = MFMA(f4, qf[6], s0); s1 = MFMA(f5, qf[6], s1);
+      s0 = MFMA(f6, qf[7], s0); s1 = MFMA(f7, qf[7], s1);
     }
     if (n_valid < BN) {
 #pragma unroll
@@ -146,29 +175,30 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
     }
 
     // ---- online softmax: this lane's query, its 32 keys; the other 32 are in lane ^ 32
-    float mx = fmaxf(s0[0], s1[0]);
+    float mx = max3(s0[0], s1[0], s0[1]);
+    mx = max3(mx, s1[1], s0[2]);
 #pragma unroll
-    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s0[v], s1[v]));
+    for (int v = 2; v < 15; ++v) mx = max3(mx, s1[v], s0[v + 1]);
+    mx = fmaxf(mx, s1[15]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
     if (__any(m_new > m_run)) {
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
       l_run *= alpha;
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
+      for (int v = 0; v < 16; ++v) { o0[v] *= alpha; o1[v] *= alpha; o2[v] *= alpha; o3[v] *= alpha; }
       m_run = m_new;
     }
     const float mc = m_run * c;
-    float psum = 0.f;
+    float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       s0[v] = __builtin_amdgcn_exp2f(fmaf(s0[v], c, -mc));
       s1[v] = __builtin_amdgcn_exp2f(fmaf(s1[v], c, -mc));
-      psum += s0[v] + s1[v];
+      ps0 += s0[v];
+      ps1 += s1[v];
     }
-    l_run += psum;
+    l_run += ps0 + ps1;
 
     // ---- P^T as B operands: k slice kk covers keys [16 kk, 16 kk + 16)
     bf16x8 pf[4];
@@ -186,15 +216,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-        const uint16_t* vp = v_rd + buf_off + 16 * kk * LSTR + 32 * dt;
-        const bf16x8 vt = read_vt(vp, vp + 8 * LSTR);
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt, pf[kk], o[dt], 0, 0, 0);
-      }
+      const uint16_t* vk = vp + 16 * kk * LSTR;
+      const bf16x8 t0 = read_vt(vk, vk + 8 * LSTR);
+      const bf16x8 t1 = read_vt(vk + 32, vk + 8 * LSTR + 32);
+      const bf16x8 t2 = read_vt(vk + 64, vk + 8 * LSTR + 64);
+      const bf16x8 t3 = read_vt(vk + 96, vk + 8 * LSTR + 96);
+      o0 = MFMA(t0, pf[kk], o0);
+      o1 = MFMA(t1, pf[kk], o1);
+      o2 = MFMA(t2, pf[kk], o2);
+      o3 = MFMA(t3, pf[kk], o3);
     }
 
-    if (has_next) stage((it + 1) & 1);
+    if (has_next) { STAGE((it + 1) & 1) }
     __syncthreads();
     r = nr; pos = npos; start = nstart; len = nlen;
   }
@@ -203,21 +236,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.f / l_tot;
   uint16_t* st = smem + wave * 32 * LSTR;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      uint2 u;
-      u.x = pack_bf16(o[dt][4 * q4] * inv, o[dt][4 * q4 + 1] * inv);
-      u.y = pack_bf16(o[dt][4 * q4 + 2] * inv, o[dt][4 * q4 + 3] * inv);
-      *(uint2*)(st + l32 * LSTR + 32 * dt + 8 * q4 + 4 * g) = u;
-    }
+#define STORE_TILE(dt_, acc_)                                                        \
+  _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) {                                 \
+    uint2 u;                                                                         \
+    u.x = pack_bf16(acc_[4 * q4] * inv, acc_[4 * q4 + 1] * inv);                     \
+    u.y = pack_bf16(acc_[4 * q4 + 2] * inv, acc_[4 * q4 + 3] * inv);                 \
+    *(uint2*)(st + l32 * LSTR + 32 * (dt_) + 8 * q4 + 4 * g) = u;                    \
+  }
+  STORE_TILE(0, o0) STORE_TILE(1, o1) STORE_TILE(2, o2) STORE_TILE(3, o3)
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int row = (lane >> 4) + 4 * i;
     if (32 * wave + row < w.n_rows)
-      *(uint4*)(O + (long)(w.row0 + 32 * wave + row) * w.row_stride + (lane & 15) * 8) =
+      *(uint4*)(O + (unsigned)(w.row0 + 32 * wave + row) * row_stride + (lane & 15) * 8) =
           *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
   }
 }
