@@ -29,9 +29,14 @@ namespace {
 constexpr int D = 128;          // head dim
 constexpr int BM = 128;         // query rows per workgroup
 constexpr int BN = 64;          // keys per LDS block
-constexpr int LSTR = 136;       // LDS row stride in elements: 256 B of data + 16 B pad
-constexpr int TILE = BN * LSTR; // elements of one K (or V) block in LDS
-constexpr int LDS_BYTES = 2 * 2 * TILE * 2;
+// LDS row strides in elements (256 B of data + pad), chosen per access pattern from a
+// bank-conflict microbenchmark: ds_read_b128 of 32 consecutive rows is conflict free at
+// 272 B, the ds_read_b64_tr_b16 pattern (4 rows x 32 B per 16 lanes) at 288 B.
+constexpr int LSTR = 136;       // K block and output staging
+constexpr int VSTR = 144;       // V block
+constexpr int KTILE = BN * LSTR;
+constexpr int STAGE_ELEMS = BN * (LSTR + VSTR);   // one K block + one V block
+constexpr int LDS_BYTES = 2 * STAGE_ELEMS * 2;
 }  // namespace
 
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
@@ -96,15 +101,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
   FETCH_ROW(3, kr3, vr3, start_, len_, pos_)
 #define STAGE(buf_)                                                       \
   {                                                                       \
-    uint16_t* kb_ = smem + (buf_)*2 * TILE + ld_row * LSTR + ld_col;      \
+    uint16_t* kb_ = smem + (buf_)*STAGE_ELEMS + ld_row * LSTR + ld_col;   \
+    uint16_t* vb_ = smem + (buf_)*STAGE_ELEMS + KTILE + ld_row * VSTR + ld_col; \
     *(uint4*)(kb_) = kr0;                                                 \
     *(uint4*)(kb_ + 16 * LSTR) = kr1;                                     \
     *(uint4*)(kb_ + 32 * LSTR) = kr2;                                     \
     *(uint4*)(kb_ + 48 * LSTR) = kr3;                                     \
-    *(uint4*)(kb_ + TILE) = vr0;                                          \
-    *(uint4*)(kb_ + TILE + 16 * LSTR) = vr1;                              \
-    *(uint4*)(kb_ + TILE + 32 * LSTR) = vr2;                              \
-    *(uint4*)(kb_ + TILE + 48 * LSTR) = vr3;                              \
+    *(uint4*)(vb_) = vr0;                                                 \
+    *(uint4*)(vb_ + 16 * VSTR) = vr1;                                     \
+    *(uint4*)(vb_ + 32 * VSTR) = vr2;                                     \
+    *(uint4*)(vb_ + 48 * VSTR) = vr3;                                     \
   }
   auto run_start = [&](int r) { return w.runs ? w.runs[2 * r] : 0; };
   auto run_len = [&](int r) { return w.runs ? w.runs[2 * r + 1] : w.single_len; };
@@ -126,7 +132,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
   // per-lane LDS read offsets
   const uint16_t* k_rd = smem + l32 * LSTR + 8 * g;
   const int t16 = lane & 15, blk = lane >> 4;
-  const uint16_t* v_rd = smem + TILE + (4 * g + (t16 >> 2)) * LSTR + 16 * (blk & 1) + 4 * (t16 & 3);
+  const uint16_t* v_rd = smem + KTILE + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3);
 
   for (int it = 0; it < n_blocks; ++it) {
     // cursor of the next block
@@ -140,8 +146,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
     if (has_next) { FETCH(nstart, nlen, npos) }
 
     const int n_valid = min(BN, len - pos);
-    const uint16_t* kp = k_rd + (it & 1) * 2 * TILE;
-    const uint16_t* vp = v_rd + (it & 1) * 2 * TILE;
+    const uint16_t* kp = k_rd + (it & 1) * STAGE_ELEMS;
+    const uint16_t* vp = v_rd + (it & 1) * STAGE_ELEMS;
 
     // ---- S^T = K Q^T for keys [0,32) and [32,64) of the block
     f32x16 s0, s1;
@@ -216,11 +222,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      const uint16_t* vk = vp + 16 * kk * LSTR;
-      const bf16x8 t0 = read_vt(vk, vk + 8 * LSTR);
-      const bf16x8 t1 = read_vt(vk + 32, vk + 8 * LSTR + 32);
-      const bf16x8 t2 = read_vt(vk + 64, vk + 8 * LSTR + 64);
-      const bf16x8 t3 = read_vt(vk + 96, vk + 8 * LSTR + 96);
+      const uint16_t* vk = vp + 16 * kk * VSTR;
+      const bf16x8 t0 = read_vt(vk, vk + 8 * VSTR);
+      const bf16x8 t1 = read_vt(vk + 32, vk + 8 * VSTR + 32);
+      const bf16x8 t2 = read_vt(vk + 64, vk + 8 * VSTR + 64);
+      const bf16x8 t3 = read_vt(vk + 96, vk + 8 * VSTR + 96);
       o0 = MFMA(t0, pf[kk], o0);
       o1 = MFMA(t1, pf[kk], o1);
       o2 = MFMA(t2, pf[kk], o2);
