@@ -13,6 +13,9 @@
 // Softmax statistics are fp32, exp via v_exp_f32 on scores pre-multiplied by log2(e).
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+#include <type_traits>
+
 #include "vorta_attn_common.h"
 
 namespace vorta {
@@ -64,9 +67,11 @@ __device__ __forceinline__ bf16x8 lds_frag(const uint16_t* p) {
 
 #define MFMA(a_, b_, c_) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b_, c_, 0, 0, 0)
 
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
+template <int NW>   // wavefronts per workgroup: 4 (two workgroups per CU) or 8 (one)
+__global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  const WorkItem w = decode_item<BM, D>(a, blockIdx.x);
+  constexpr int STG_ROWS = 4 * NW, STG_PASSES = BN / STG_ROWS;   // staging: rows per pass, passes per block
+  const WorkItem w = decode_item<32 * NW, D>(a, blockIdx.x);
   const uint16_t* Q = (const uint16_t*)(w.seg == 0 ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
   const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
   const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
@@ -90,27 +95,31 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
   uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
 #define FETCH_ROW(i_, kr_, vr_, start_, len_, pos_)                                        \
   {                                                                                        \
-    const unsigned off_ = (unsigned)((start_) + min((pos_) + ld_row + 16 * (i_), (len_)-1)) * row_stride + ld_col; \
+    const unsigned off_ = (unsigned)((start_) + min((pos_) + ld_row + STG_ROWS * (i_), (len_)-1)) * row_stride + ld_col; \
     kr_ = *(const uint4*)(K + off_);                                                       \
     vr_ = *(const uint4*)(V + off_);                                                       \
   }
-#define FETCH(start_, len_, pos_)                  \
-  FETCH_ROW(0, kr0, vr0, start_, len_, pos_)       \
-  FETCH_ROW(1, kr1, vr1, start_, len_, pos_)       \
-  FETCH_ROW(2, kr2, vr2, start_, len_, pos_)       \
-  FETCH_ROW(3, kr3, vr3, start_, len_, pos_)
+#define FETCH(start_, len_, pos_)                      \
+  FETCH_ROW(0, kr0, vr0, start_, len_, pos_)           \
+  FETCH_ROW(1, kr1, vr1, start_, len_, pos_)           \
+  if constexpr (STG_PASSES == 4) {                     \
+    FETCH_ROW(2, kr2, vr2, start_, len_, pos_)         \
+    FETCH_ROW(3, kr3, vr3, start_, len_, pos_)         \
+  }
 #define STAGE(buf_)                                                       \
   {                                                                       \
     uint16_t* kb_ = smem + (buf_)*STAGE_ELEMS + ld_row * LSTR + ld_col;   \
     uint16_t* vb_ = smem + (buf_)*STAGE_ELEMS + KTILE + ld_row * VSTR + ld_col; \
     *(uint4*)(kb_) = kr0;                                                 \
-    *(uint4*)(kb_ + 16 * LSTR) = kr1;                                     \
-    *(uint4*)(kb_ + 32 * LSTR) = kr2;                                     \
-    *(uint4*)(kb_ + 48 * LSTR) = kr3;                                     \
+    *(uint4*)(kb_ + STG_ROWS * LSTR) = kr1;                               \
     *(uint4*)(vb_) = vr0;                                                 \
-    *(uint4*)(vb_ + 16 * VSTR) = vr1;                                     \
-    *(uint4*)(vb_ + 32 * VSTR) = vr2;                                     \
-    *(uint4*)(vb_ + 48 * VSTR) = vr3;                                     \
+    *(uint4*)(vb_ + STG_ROWS * VSTR) = vr1;                               \
+    if constexpr (STG_PASSES == 4) {                                      \
+      *(uint4*)(kb_ + 2 * STG_ROWS * LSTR) = kr2;                         \
+      *(uint4*)(kb_ + 3 * STG_ROWS * LSTR) = kr3;                         \
+      *(uint4*)(vb_ + 2 * STG_ROWS * VSTR) = vr2;                         \
+      *(uint4*)(vb_ + 3 * STG_ROWS * VSTR) = vr3;                         \
+    }                                                                     \
   }
   auto run_start = [&](int r) { return w.runs ? w.runs[2 * r] : 0; };
   auto run_len = [&](int r) { return w.runs ? w.runs[2 * r + 1] : w.single_len; };
@@ -260,21 +269,307 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const AttnArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Long-key-loop variant for the dense and core-set segments: 64 query rows per wavefront
+// (two 32-row column blocks A and B), 256 rows per workgroup, one workgroup per CU.  Every K
+// and V^T fragment read from LDS feeds two MFMAs, which halves the LDS traffic per FLOP -- the
+// limiter of the 32-row kernel -- and the two blocks give the wavefront independent work to
+// overlap softmax arithmetic with matrix instructions.
+// ------------------------------------------------------------------------------------------
+namespace {
+constexpr int BM2 = 256;
+}
+
+// Softmax bookkeeping of the long-loop kernel ("lazy reference"): probabilities are taken
+// relative to a per-query reference m_ref instead of the running maximum,
+//     P' = exp2((s - m_ref) * scale * log2 e),   O' = sum P' V,   l' = sum P',   O = O' / l',
+// which is the same quotient as long as nothing overflows.  The hot loop therefore never
+// touches the O accumulators with vector ALU instructions.  When any score of a step exceeds
+// m_ref by more than REF_SLACK (in log2 units, P' <= 2^REF_SLACK), the wavefront leaves the hot
+// loop BEFORE using that step, raises m_ref to the running maximum, rescales O' and l' once,
+// and re-enters the loop at the same step.  The first step always takes that path (m_ref
+// starts at -inf).
+constexpr float REF_SLACK = 8.0f;
+
+__device__ __forceinline__ float max16(const f32x16& s) {
+  float mx = max3(s[0], s[1], s[2]);
+#pragma unroll
+  for (int v = 3; v < 15; v += 2) mx = max3(mx, s[v], s[v + 1]);
+  return fmaxf(mx, s[15]);
+}
+
+__device__ __forceinline__ void exp_pack(f32x16& s, float c, float mc, float& l, bf16x8& p0, bf16x8& p1) {
+  float ps = 0.f;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], c, -mc));
+    ps += s[v];
+  }
+  l += ps;
+  uint4 u0, u1;
+  u0.x = pack_bf16(s[0], s[1]); u0.y = pack_bf16(s[2], s[3]); u0.z = pack_bf16(s[4], s[5]); u0.w = pack_bf16(s[6], s[7]);
+  u1.x = pack_bf16(s[8], s[9]); u1.y = pack_bf16(s[10], s[11]); u1.z = pack_bf16(s[12], s[13]); u1.w = pack_bf16(s[14], s[15]);
+  p0 = __builtin_bit_cast(bf16x8, u0);
+  p1 = __builtin_bit_cast(bf16x8, u1);
+}
+
+__global__ __launch_bounds__(256, 1) void attn_bf16_m64_kernel(const AttnArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  constexpr int STG_ROWS = 16, STG_PASSES = 4;
+  const WorkItem w = decode_item<BM2, D>(a, blockIdx.x);
+  const uint16_t* Q = (const uint16_t*)(w.seg == 0 ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
+  const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
+  const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
+  uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
+  const unsigned row_stride = (unsigned)w.row_stride;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  bf16x8 qa[8], qb[8];
+  {
+    const unsigned ra = w.row0 + min(64 * wave + l32, w.n_rows - 1);
+    const unsigned rb = w.row0 + min(64 * wave + 32 + l32, w.n_rows - 1);
+    const uint16_t* pa = Q + ra * row_stride + 8 * g;
+    const uint16_t* pb = Q + rb * row_stride + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      qa[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(pa + 16 * ks));
+      qb[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(pb + 16 * ks));
+    }
+  }
+
+  const int ld_row = tid >> 4, ld_col = (tid & 15) * 8;
+  uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
+  auto run_start = [&](int r) { return w.runs ? w.runs[2 * r] : 0; };
+  auto run_len = [&](int r) { return w.runs ? w.runs[2 * r + 1] : w.single_len; };
+  int n_blocks = 0;
+  for (int r = 0; r < w.n_runs; ++r) n_blocks += (run_len(r) + BN - 1) / BN;
+
+  f32x16 a0, a1, a2, a3, b0, b1, b2, b3;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    a0[v] = 0.f; a1[v] = 0.f; a2[v] = 0.f; a3[v] = 0.f;
+    b0[v] = 0.f; b1[v] = 0.f; b2[v] = 0.f; b3[v] = 0.f;
+  }
+  const float c = a.scale * 1.4426950408889634f;
+  const float slack = REF_SLACK / c;                 // REF_SLACK in raw score units
+  float mrefA = -INFINITY, mrefB = -INFINITY;        // per-query reference (same in lanes l, l^32)
+  float mrunA = -INFINITY, mrunB = -INFINITY;        // this lane's running max (raw scores)
+  float lA = 0.f, lB = 0.f;
+
+  int r = 0, pos = 0, start = run_start(0), len = run_len(0);
+  int nr = 0, npos = 0, nstart = 0, nlen = 0;
+  FETCH(start, len, 0)
+  STAGE(0)
+  __syncthreads();
+
+  const uint16_t* k_rd = smem + l32 * LSTR + 8 * g;
+  const int t16 = lane & 15, blk = lane >> 4;
+  const uint16_t* v_rd = smem + KTILE + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3);
+
+  const int n_steps = 2 * n_blocks;     // 32-key steps; two per LDS stage
+  int j = 0;
+  bool fetched = false;                 // next stage already requested (survives a re-entry)
+  // FENCE pins the instruction order to the order written here -- a matrix instruction, then
+  // a handful of vector instructions -- so a single wavefront keeps both pipes busy
+  // (instructions issue in order).  PIN keeps speculative work on its side of a branch.
+#define FENCE() __builtin_amdgcn_sched_barrier(0)
+#define PIN(x_) asm volatile("" : "+v"(x_))
+  while (j < n_steps) {
+    bool raise = false;
+    // -------- hot loop: no vector ALU instruction touches a*, b* in here --------
+    // Step order: QK_A; QK_B with exp(A) in its shadow (speculative: uses the current reference
+    // and is discarded if the check fails); reference check; PV_A with exp(B) in its shadow; PV_B.
+    for (; j < n_steps; ++j) {
+      const int it = j >> 1, h = j & 1;
+      if (h == 0 && !fetched) {
+        nr = r; npos = pos + BN; nstart = start; nlen = len;
+        if (npos >= len) {
+          nr = r + 1;
+          npos = 0;
+          if (nr < w.n_runs) { nstart = run_start(nr); nlen = run_len(nr); }
+        }
+        if (it + 1 < n_blocks) { FETCH(nstart, nlen, npos) }
+        fetched = true;
+      }
+      // Keys past the end of a run are copies of its last row, so they never raise a row
+      // maximum; only their probabilities have to be zeroed.
+      const int n_valid = min(BN, len - pos) - 32 * h;     // valid keys of this step (may be <= 0)
+      const uint16_t* kp = k_rd + (it & 1) * STAGE_ELEMS + 32 * h * LSTR;
+      const uint16_t* vp = v_rd + (it & 1) * STAGE_ELEMS + 32 * h * VSTR;
+      bf16x8 f[8];
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) f[ks] = lds_frag(kp + 16 * ks);
+      bf16x8 t[2][4];
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+          t[kk][dt] = read_vt(vp + 16 * kk * VSTR + 32 * dt, vp + (16 * kk + 8) * VSTR + 32 * dt);
+      f32x16 sA, sB;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { sA[v] = 0.f; sB[v] = 0.f; }
+      FENCE();
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) sA = MFMA(f[ks], qa[ks], sA);
+      FENCE();
+      const float mxA = max16(sA);
+      const float mcA = mrefA * c, mcB = mrefB * c;
+      float eA[16], eB[16];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        FENCE();
+        sB = MFMA(f[i], qb[i], sB);
+        FENCE();
+        eA[2 * i] = __builtin_amdgcn_exp2f(fmaf(sA[2 * i], c, -mcA));
+        eA[2 * i + 1] = __builtin_amdgcn_exp2f(fmaf(sA[2 * i + 1], c, -mcA));
+        PIN(eA[2 * i]);
+        PIN(eA[2 * i + 1]);
+      }
+      FENCE();
+      const float mxB = max16(sB);
+      mrunA = fmaxf(mrunA, mxA);
+      mrunB = fmaxf(mrunB, mxB);
+      if (__any(mxA > mrefA + slack || mxB > mrefB + slack)) {
+        raise = true;
+        break;                                            // step j is redone after the rescale
+      }
+      if (n_valid < 32) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (8 * (v >> 2) + 4 * g + (v & 3) >= n_valid) eA[v] = 0.f;
+      }
+      {
+        float ps = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ps += eA[v];
+        lA += ps;
+      }
+      const bf16x8 pa0 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(eA[0], eA[1]), pack_bf16(eA[2], eA[3]),
+                                                                pack_bf16(eA[4], eA[5]), pack_bf16(eA[6], eA[7])));
+      const bf16x8 pa1 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(eA[8], eA[9]), pack_bf16(eA[10], eA[11]),
+                                                                pack_bf16(eA[12], eA[13]), pack_bf16(eA[14], eA[15])));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        FENCE();
+        const bf16x8 pA = (i >> 2) ? pa1 : pa0;
+        switch (i & 3) {
+          case 0: a0 = MFMA(t[i >> 2][0], pA, a0); break;
+          case 1: a1 = MFMA(t[i >> 2][1], pA, a1); break;
+          case 2: a2 = MFMA(t[i >> 2][2], pA, a2); break;
+          default: a3 = MFMA(t[i >> 2][3], pA, a3); break;
+        }
+        FENCE();
+        eB[2 * i] = __builtin_amdgcn_exp2f(fmaf(sB[2 * i], c, -mcB));
+        eB[2 * i + 1] = __builtin_amdgcn_exp2f(fmaf(sB[2 * i + 1], c, -mcB));
+      }
+      FENCE();
+      if (n_valid < 32) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (8 * (v >> 2) + 4 * g + (v & 3) >= n_valid) eB[v] = 0.f;
+      }
+      {
+        float ps = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ps += eB[v];
+        lB += ps;
+      }
+      const bf16x8 pb0 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(eB[0], eB[1]), pack_bf16(eB[2], eB[3]),
+                                                                pack_bf16(eB[4], eB[5]), pack_bf16(eB[6], eB[7])));
+      const bf16x8 pb1 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(eB[8], eB[9]), pack_bf16(eB[10], eB[11]),
+                                                                pack_bf16(eB[12], eB[13]), pack_bf16(eB[14], eB[15])));
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 pB = kk ? pb1 : pb0;
+        b0 = MFMA(t[kk][0], pB, b0);
+        b1 = MFMA(t[kk][1], pB, b1);
+        b2 = MFMA(t[kk][2], pB, b2);
+        b3 = MFMA(t[kk][3], pB, b3);
+      }
+      if (h == 1) {
+        if (it + 1 < n_blocks) { STAGE((it + 1) & 1) }
+        __syncthreads();
+        r = nr; pos = npos; start = nstart; len = nlen;
+        fetched = false;
+      }
+    }
+    if (!raise) break;
+    // ---------------- cold path: raise the references to the running maxima ----------------
+    {
+      const float newA = fmaxf(mrunA, __shfl_xor(mrunA, 32, 64));
+      const float newB = fmaxf(mrunB, __shfl_xor(mrunB, 32, 64));
+      const float alA = __builtin_amdgcn_exp2f((mrefA - newA) * c);   // 0 on the first pass (m_ref = -inf)
+      const float alB = __builtin_amdgcn_exp2f((mrefB - newB) * c);
+      lA *= alA;
+      lB *= alB;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        a0[v] *= alA; a1[v] *= alA; a2[v] *= alA; a3[v] *= alA;
+        b0[v] *= alB; b1[v] *= alB; b2[v] *= alB; b3[v] *= alB;
+      }
+      mrefA = newA;
+      mrefB = newB;
+    }
+  }
+#undef FENCE
+#undef PIN
+
+  // ---- epilogue: two passes (block A, block B) through a per-wave LDS staging area
+  uint16_t* st = smem + wave * 32 * LSTR;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const float l_run = half ? lB : lA;
+    const float inv = 1.f / (l_run + __shfl_xor(l_run, 32, 64));
+    if (half == 0) { STORE_TILE(0, a0) STORE_TILE(1, a1) STORE_TILE(2, a2) STORE_TILE(3, a3) }
+    else { STORE_TILE(0, b0) STORE_TILE(1, b1) STORE_TILE(2, b2) STORE_TILE(3, b3) }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = (lane >> 4) + 4 * i;
+      const int qrow = 64 * wave + 32 * half + row;
+      if (qrow < w.n_rows)
+        *(uint4*)(O + (unsigned)(w.row0 + qrow) * row_stride + (lane & 15) * 8) =
+            *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+    }
+    __syncthreads();
+  }
+}
+
+static int g_long_variant = getenv("VORTA_LONG_VARIANT") ? atoi(getenv("VORTA_LONG_VARIANT")) : 0;   // experiment switch
+
+static int set_lds_limit(const void* kernel, const char* name) {
+  hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  if (e != hipSuccess) return fail(VORTA_EHIP, "hipFuncSetAttribute(%s, %d B LDS): %s", name, LDS_BYTES, hipGetErrorString(e));
+  return VORTA_OK;
+}
+
 int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream) {
-  AttnArgs a;
-  if (int rc = fill_attn_args(p, rl, io, BM, &a)) return rc;
-  if (a.end_text == 0) return VORTA_OK;
   static std::once_flag once;
-  static hipError_t attr_err = hipSuccess;
+  static int attr_rc = VORTA_OK;
   std::call_once(once, [] {
-    attr_err = hipFuncSetAttribute((const void*)attn_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   LDS_BYTES);
+    attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4>, "attn_bf16_kernel<4>");
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_kernel<8>, "attn_bf16_kernel<8>");
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_m64_kernel, "attn_bf16_m64_kernel");
   });
-  if (attr_err != hipSuccess)
-    return fail(VORTA_EHIP, "hipFuncSetAttribute(dynamic LDS %d): %s", LDS_BYTES, hipGetErrorString(attr_err));
-  hipLaunchKernelGGL(attn_bf16_kernel, dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+  if (attr_rc) return attr_rc;
+  // dense + core-set heads: 256-row workgroups; window heads: 128-row workgroups (one tile each)
+  RouteLists long_rl = rl, win_rl = rl;
+  long_rl.count[1] = 0;
+  win_rl.count[0] = win_rl.count[2] = 0;
+  AttnArgs a;
+  if (int rc = fill_attn_args(p, long_rl, io, BM2, &a)) return rc;
+  if (a.end_text > 0) {
+    if (g_long_variant == 1)
+      hipLaunchKernelGGL(attn_bf16_m64_kernel, dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+    else
+      hipLaunchKernelGGL(attn_bf16_kernel<8>, dim3(a.end_text), dim3(512), LDS_BYTES, (hipStream_t)stream, a);
+  }
+  if (int rc = fill_attn_args(p, win_rl, io, BM, &a)) return rc;
+  if (a.end_text > 0) hipLaunchKernelGGL(attn_bf16_kernel<4>, dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(VORTA_EHIP, "launch of attn_bf16_kernel: %s", hipGetErrorString(e));
+  if (e != hipSuccess) return fail(VORTA_EHIP, "launch of attn_bf16 kernels: %s", hipGetErrorString(e));
   return VORTA_OK;
 }
 
