@@ -537,6 +537,263 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_m64_kernel(const AttnArgs a)
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Ping-pong variant for the dense and core-set segments.  Eight wavefronts of 32 query rows;
+// the SIMD that hosts wavefronts w and w+4 sees them in opposite phases:
+//     M phase   O^T += V^T P^T of the previous key block, then S^T = K Q^T of the current one
+//               (32 matrix instructions, all LDS fragment reads)
+//     V phase   softmax arithmetic of the current block (exp, sums, bf16 packing), plus the
+//               global -> LDS staging two blocks ahead
+// with a workgroup barrier at every phase change and the upper four wavefronts started half an
+// iteration late, so the matrix pipe of a SIMD is fed by one wavefront while the vector pipe
+// works for the other.  Softmax uses the lazy per-query reference (see REF_SLACK above); the
+// O rescale runs only when a reference has to be raised.  Four LDS stages keep the block being
+// written apart from the two being read by either group.
+// ------------------------------------------------------------------------------------------
+namespace {
+constexpr int PP_BUFS = 4;
+constexpr int PP_LDS_BYTES = PP_BUFS * STAGE_ELEMS * 2;
+}  // namespace
+
+#ifdef VORTA_PP_TIMING   // debug build: per-phase wall-clock (100 MHz ticks) of wavefronts 0 and 4 of block 0
+__device__ long long g_pp_timing[2][16];
+#define PP_T_DECL long long tacc_[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; long long tprev_ = __builtin_amdgcn_s_memrealtime();
+#define PP_T_MARK(i_) { const long long now_ = __builtin_amdgcn_s_memrealtime(); tacc_[i_] += now_ - tprev_; tprev_ = now_; }
+#define PP_T_DUMP if (blockIdx.x == 0 && lane == 0 && (wave == 0 || wave == 4)) { for (int i = 0; i < 12; ++i) g_pp_timing[wave >> 2][i] = tacc_[i]; g_pp_timing[wave >> 2][15] = n_blocks; }
+#else
+#define PP_T_DECL
+#define PP_T_MARK(i_)
+#define PP_T_DUMP
+#endif
+
+__global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(const AttnArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  constexpr int STG_ROWS = 32, STG_PASSES = 2;
+  const WorkItem w = decode_item<BM2, D>(a, blockIdx.x);
+  const uint16_t* Q = (const uint16_t*)(w.seg == 0 ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
+  const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
+  const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
+  uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
+  const unsigned row_stride = (unsigned)w.row_stride;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int grp = wave >> 2;
+
+  bf16x8 qf[8];
+  {
+    const unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    const uint16_t* qp = Q + qrow * row_stride + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * ks));
+  }
+
+  const int ld_row = tid >> 4, ld_col = (tid & 15) * 8;
+  uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
+  auto run_start = [&](int r) { return w.runs ? w.runs[2 * r] : 0; };
+  auto run_len = [&](int r) { return w.runs ? w.runs[2 * r + 1] : w.single_len; };
+  int n_blocks = 0;
+  for (int r = 0; r < w.n_runs; ++r) n_blocks += (run_len(r) + BN - 1) / BN;
+
+  // fetch cursor (block being requested) and compute cursor (block being used)
+  int fr = 0, fpos = 0, fstart = run_start(0), flen = run_len(0);
+  int cr = 0, cpos = 0, clen = flen;
+#define FETCH_NEXT()                                                     \
+  {                                                                      \
+    FETCH(fstart, flen, fpos)                                            \
+    fpos += BN;                                                          \
+    if (fpos >= flen) {                                                  \
+      ++fr;                                                              \
+      fpos = 0;                                                          \
+      if (fr < w.n_runs) { fstart = run_start(fr); flen = run_len(fr); } \
+    }                                                                    \
+  }
+  FETCH_NEXT()
+  STAGE(0)
+  if (n_blocks > 1) {
+    FETCH_NEXT()
+    STAGE(1)
+  }
+  if (n_blocks > 2) { FETCH_NEXT() }          // block 2 waits in registers
+  __syncthreads();
+  if (grp == 1) __syncthreads();              // upper group runs half an iteration behind
+
+  f32x16 o0, o1, o2, o3;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { o0[v] = 0.f; o1[v] = 0.f; o2[v] = 0.f; o3[v] = 0.f; }
+  const float c = a.scale * 1.4426950408889634f;
+  const float slack = REF_SLACK / c;
+  float m_ref = -INFINITY, m_run = -INFINITY, l_run = 0.f;
+  bf16x8 pf[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) pf[i] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+
+  const uint16_t* k_rd = smem + l32 * LSTR + 8 * g;
+  const int t16 = lane & 15, blk = lane >> 4;
+  const uint16_t* v_rd = smem + KTILE + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3);
+
+  f32x16 oacc[4] = {o0, o1, o2, o3};
+  f32x16 sacc[2];
+  bf16x8 frag[32];            // fragment of matrix-instruction slot i: slots 0..15 = V^T for PV, 16..31 = K for QK
+  // LDS fragment of slot i.  PV slot (kk, dt) = (i / 4, i % 4) of stage `sv`; QK slot (ks, sb) = ((i - 16) / 2, i % 2)
+  // of stage `sk`.
+#define LOAD_SLOT(i_, vp_, kp_)                                                                   \
+  {                                                                                               \
+    if ((i_) < 16) {                                                                              \
+      const uint16_t* a_ = (vp_) + 16 * ((i_) >> 2) * VSTR + 32 * ((i_)&3);                       \
+      frag[i_] = read_vt(a_, a_ + 8 * VSTR);                                                        \
+    } else {                                                                                      \
+      frag[i_] = lds_frag((kp_) + 32 * ((i_)&1) * LSTR + 16 * (((i_)-16) >> 1));                    \
+    }                                                                                             \
+  }
+#define MFMA_SLOT(i_)                                                                             \
+  {                                                                                               \
+    if ((i_) < 16) oacc[(i_)&3] = MFMA(frag[i_], pf[(i_) >> 2], oacc[(i_)&3]);                      \
+    else sacc[(i_)&1] = MFMA(frag[i_], qf[((i_)-16) >> 1], sacc[(i_)&1]);                           \
+  }
+  PP_T_DECL
+  constexpr int LEAD = 8;   // fragments requested this many matrix instructions ahead of their use
+
+  // V phase of block j: softmax arithmetic on sacc -> pf, staging two blocks ahead, and the
+  // first LEAD fragment requests of the next M phase (PV of this block) so they are in flight
+  // across the barrier.
+  auto v_phase = [&](int j) {
+    f32x16& s0 = sacc[0];
+    f32x16& s1 = sacc[1];
+    const int n_valid = min(BN, clen - cpos);
+    cpos += BN;
+    if (cpos >= clen) {
+      ++cr;
+      cpos = 0;
+      if (cr < w.n_runs) clen = run_len(cr);
+    }
+    // rows past the end of a run repeat its last row: they cannot raise a maximum, only
+    // their probabilities are zeroed below
+    float mx = max3(s0[0], s1[0], s0[1]);
+    mx = max3(mx, s1[1], s0[2]);
+#pragma unroll
+    for (int v = 2; v < 15; ++v) mx = max3(mx, s1[v], s0[v + 1]);
+    mx = fmaxf(mx, s1[15]);
+    m_run = fmaxf(m_run, mx);
+    PP_T_MARK(5)
+    if (__any(mx > m_ref + slack)) {
+      const float m_new = fmaxf(m_run, __shfl_xor(m_run, 32, 64));
+      const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);   // 0 the first time
+      l_run *= alpha;
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[d][v] *= alpha;
+      m_ref = m_new;
+    }
+    PP_T_MARK(6)
+    const float mc = m_ref * c;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      s0[v] = __builtin_amdgcn_exp2f(fmaf(s0[v], c, -mc));
+      s1[v] = __builtin_amdgcn_exp2f(fmaf(s1[v], c, -mc));
+    }
+    if (n_valid < BN) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = 8 * (v >> 2) + 4 * g + (v & 3);
+        if (key >= n_valid) s0[v] = 0.f;
+        if (key + 32 >= n_valid) s1[v] = 0.f;
+      }
+    }
+    float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { ps0 += s0[v]; ps1 += s1[v]; }
+    l_run += ps0 + ps1;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint4 u0, u1;
+      u0.x = pack_bf16(s0[8 * h + 0], s0[8 * h + 1]); u0.y = pack_bf16(s0[8 * h + 2], s0[8 * h + 3]);
+      u0.z = pack_bf16(s0[8 * h + 4], s0[8 * h + 5]); u0.w = pack_bf16(s0[8 * h + 6], s0[8 * h + 7]);
+      u1.x = pack_bf16(s1[8 * h + 0], s1[8 * h + 1]); u1.y = pack_bf16(s1[8 * h + 2], s1[8 * h + 3]);
+      u1.z = pack_bf16(s1[8 * h + 4], s1[8 * h + 5]); u1.w = pack_bf16(s1[8 * h + 6], s1[8 * h + 7]);
+      pf[h] = __builtin_bit_cast(bf16x8, u0);
+      pf[2 + h] = __builtin_bit_cast(bf16x8, u1);
+    }
+    PP_T_MARK(7)
+    if (j + 2 < n_blocks) { STAGE((j + 2) & 3) }
+    PP_T_MARK(8)
+    if (j + 3 < n_blocks) { FETCH_NEXT() }
+    PP_T_MARK(9)
+    const uint16_t* vp = v_rd + (j & 3) * STAGE_ELEMS;
+#pragma unroll
+    for (int i = 0; i < LEAD; ++i) LOAD_SLOT(i, vp, vp)
+  };
+
+  // ---- block 0: QK only
+  {
+    const uint16_t* kp = k_rd;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sacc[0][v] = 0.f; sacc[1][v] = 0.f; }
+#pragma unroll
+    for (int i = 16; i < 32; ++i) LOAD_SLOT(i, kp, kp)
+#pragma unroll
+    for (int i = 16; i < 32; ++i) MFMA_SLOT(i)
+  }
+  __syncthreads();
+  v_phase(0);
+  __syncthreads();
+  // ---- blocks 1 .. n-1: PV of the previous block, then QK of this one, one fragment stream
+  for (int j = 1; j < n_blocks; ++j) {
+    PP_T_MARK(0)
+    const uint16_t* vp = v_rd + ((j - 1) & 3) * STAGE_ELEMS;
+    const uint16_t* kp = k_rd + (j & 3) * STAGE_ELEMS;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      if (i == 16) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { sacc[0][v] = 0.f; sacc[1][v] = 0.f; }
+      }
+      MFMA_SLOT(i)
+      if (i + LEAD < 32) LOAD_SLOT(i + LEAD, vp, kp)
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    PP_T_MARK(1)
+    __syncthreads();
+    PP_T_MARK(2)
+    v_phase(j);
+    PP_T_MARK(3)
+    __syncthreads();
+    PP_T_MARK(4)
+  }
+  // ---- PV of the last block
+  {
+    const uint16_t* vp = v_rd + ((n_blocks - 1) & 3) * STAGE_ELEMS;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      MFMA_SLOT(i)
+      if (i + LEAD < 16) LOAD_SLOT(i + LEAD, vp, vp)
+    }
+  }
+  __syncthreads();
+  __syncthreads();
+  if (grp == 0) __syncthreads();
+  PP_T_DUMP
+  o0 = oacc[0]; o1 = oacc[1]; o2 = oacc[2]; o3 = oacc[3];
+#undef LOAD_SLOT
+#undef MFMA_SLOT
+#undef FETCH_NEXT
+
+  // ---- epilogue: normalise, transpose through LDS, store whole rows
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.f / l_tot;
+  uint16_t* st = smem + wave * 32 * LSTR;
+  STORE_TILE(0, o0) STORE_TILE(1, o1) STORE_TILE(2, o2) STORE_TILE(3, o3)
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = (lane >> 4) + 4 * i;
+    if (32 * wave + row < w.n_rows)
+      *(uint4*)(O + (unsigned)(w.row0 + 32 * wave + row) * row_stride + (lane & 15) * 8) =
+          *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+  }
+}
+
 static int g_long_variant = getenv("VORTA_LONG_VARIANT") ? atoi(getenv("VORTA_LONG_VARIANT")) : 0;   // experiment switch
 
 static int set_lds_limit(const void* kernel, const char* name) {
@@ -552,6 +809,10 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
     attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4>, "attn_bf16_kernel<4>");
     if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_kernel<8>, "attn_bf16_kernel<8>");
     if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_m64_kernel, "attn_bf16_m64_kernel");
+    if (!attr_rc) {
+      hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_pp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, PP_LDS_BYTES);
+      if (e != hipSuccess) attr_rc = fail(VORTA_EHIP, "hipFuncSetAttribute(attn_bf16_pp_kernel): %s", hipGetErrorString(e));
+    }
   });
   if (attr_rc) return attr_rc;
   // dense + core-set heads: 256-row workgroups; window heads: 128-row workgroups (one tile each)
@@ -563,6 +824,8 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   if (a.end_text > 0) {
     if (g_long_variant == 1)
       hipLaunchKernelGGL(attn_bf16_m64_kernel, dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+    else if (g_long_variant == 2)
+      hipLaunchKernelGGL(attn_bf16_pp_kernel, dim3(a.end_text), dim3(512), PP_LDS_BYTES, (hipStream_t)stream, a);
     else
       hipLaunchKernelGGL(attn_bf16_kernel<8>, dim3(a.end_text), dim3(512), LDS_BYTES, (hipStream_t)stream, a);
   }
@@ -574,3 +837,9 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
 }
 
 }  // namespace vorta
+
+#ifdef VORTA_PP_TIMING
+extern "C" int vorta_debug_pp_timing(long long* out16) {
+  return hipMemcpyFromSymbol(out16, HIP_SYMBOL(vorta::g_pp_timing), sizeof(long long) * 32) == hipSuccess ? 0 : -6;
+}
+#endif
