@@ -65,6 +65,23 @@ __device__ __forceinline__ bf16x8 lds_frag(const uint16_t* p) {
   return __builtin_bit_cast(bf16x8, *(const uint4*)p);
 }
 
+// LDS-address-space pointer flavours: a 32-bit base register plus immediate offsets.
+typedef __attribute__((address_space(3))) const uint16_t* lds_ptr;
+typedef __attribute__((address_space(3))) const uint4* lds_u4_ptr;
+__device__ __forceinline__ bf16x8 lds_frag3(lds_ptr p) { return __builtin_bit_cast(bf16x8, *(lds_u4_ptr)p); }
+__device__ __forceinline__ bf16x8 read_vt3(lds_ptr p_lo, lds_ptr p_hi) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p_lo);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p_hi);
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+// Hide how a per-sub-step LDS base was computed, so every fragment read is base + immediate
+// instead of one precomputed address register per fragment.
+__device__ __forceinline__ lds_ptr opaque(lds_ptr p) {
+  asm volatile("" : "+v"(p));
+  return p;
+}
+
 #define MFMA(a_, b_, c_) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b_, c_, 0, 0, 0)
 
 template <int NW>   // wavefronts per workgroup: 4 (two workgroups per CU) or 8 (one)
@@ -794,6 +811,230 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pp_kernel(const AttnArgs a) 
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Interleaved variant for the dense and core-set segments.  Measurements on gfx950: vector
+// instructions issued by the SAME wavefront right behind a matrix instruction run in its shadow
+// (about six per v_mfma_f32_32x32x16_bf16, an exp counting double), while vector work of
+// another wavefront on the SIMD mostly serialises with it.  So every wavefront software-
+// pipelines its own loop over 32-key sub-steps t:
+//     matrix pipe   QK of sub-step t+1 (8 instr.)  then  PV of sub-step t-1 (8 instr.)
+//     vector pipe   exp / sum / bf16 packing of sub-step t, then the row maximum of t+1,
+//                   a few instructions behind each matrix instruction
+// with LDS fragments requested IL_LEAD matrix instructions ahead (the first ones of a sub-step
+// at the end of the previous one).  Eight wavefronts of 32 query rows share 64-key LDS stages,
+// three buffers, one barrier per stage.  Softmax uses the lazy per-query reference (REF_SLACK).
+// ------------------------------------------------------------------------------------------
+namespace {
+constexpr int IL_BUFS = 3;
+constexpr int IL_LDS_BYTES = IL_BUFS * STAGE_ELEMS * 2;
+constexpr int IL_LEAD = 4;
+}  // namespace
+
+__global__ __launch_bounds__(512, 1) void attn_bf16_il_kernel(const AttnArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  constexpr int STG_ROWS = 32, STG_PASSES = 2;
+  const WorkItem w = decode_item<BM2, D>(a, blockIdx.x);
+  const uint16_t* Q = (const uint16_t*)(w.seg == 0 ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
+  const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
+  const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
+  uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
+  const unsigned row_stride = (unsigned)w.row_stride;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  bf16x8 qf[8];
+  {
+    const unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    const uint16_t* qp = Q + qrow * row_stride + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * ks));
+  }
+
+  const int ld_row = tid >> 4, ld_col = (tid & 15) * 8;
+  uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
+  auto run_start = [&](int r) { return w.runs ? w.runs[2 * r] : 0; };
+  auto run_len = [&](int r) { return w.runs ? w.runs[2 * r + 1] : w.single_len; };
+  int n_blocks = 0;
+  for (int r = 0; r < w.n_runs; ++r) n_blocks += (run_len(r) + BN - 1) / BN;
+
+  int fr = 0, fpos = 0, fstart = run_start(0), flen = run_len(0);   // fetch cursor
+  int cr = 0, cpos = 0, clen = flen;                                 // compute cursor
+#define FETCH_NEXT()                                                     \
+  {                                                                      \
+    FETCH(fstart, flen, fpos)                                            \
+    fpos += BN;                                                          \
+    if (fpos >= flen) {                                                  \
+      ++fr;                                                              \
+      fpos = 0;                                                          \
+      if (fr < w.n_runs) { fstart = run_start(fr); flen = run_len(fr); } \
+    }                                                                    \
+  }
+  FETCH_NEXT()
+  STAGE(0)
+  if (n_blocks > 1) { FETCH_NEXT() }          // stage 1 waits in registers
+  __syncthreads();
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[d][v] = 0.f;
+  const float c = a.scale * 1.4426950408889634f;
+  const float slack = REF_SLACK / c;
+  float m_ref = -INFINITY, m_run = -INFINITY, l_run = 0.f;
+
+  const lds_ptr k_rd = (lds_ptr)(smem + l32 * LSTR + 8 * g);
+  const int t16 = lane & 15, blk = lane >> 4;
+  const lds_ptr v_rd = (lds_ptr)(smem + KTILE + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3));
+
+  // scores of sub-step 0 and the first fragments of sub-step 0's matrix work (QK of sub-step 1)
+  f32x16 s_even, s_odd;     // scores of even / odd sub-steps
+#pragma unroll
+  for (int v = 0; v < 16; ++v) s_even[v] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) s_even = MFMA(lds_frag3(k_rd + 16 * ks), qf[ks], s_even);
+  float mx_cur = max16(s_even);
+  bf16x8 pre[IL_LEAD];
+#pragma unroll
+  for (int i = 0; i < IL_LEAD; ++i) pre[i] = lds_frag3(k_rd + 32 * LSTR + 16 * i);
+  bf16x8 p_prev[2];
+  p_prev[0] = p_prev[1] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+
+  // One 32-key sub-step.  kq: K fragments of sub-step t+1; vq: V fragments of sub-step t-1;
+  // kn: K fragments of sub-step t+2 (first IL_LEAD requested at the end); n_valid: valid keys of
+  // sub-step t.  FAST pins the instruction order; the other copy handles run tails.
+  auto substep = [&](auto fast_tag, f32x16& s_cur, f32x16& s_next, lds_ptr kq, lds_ptr vq, int n_valid) {
+    constexpr bool FAST = decltype(fast_tag)::value;
+#define IL_FENCE() do { if (FAST) __builtin_amdgcn_sched_barrier(0); } while (0)
+    m_run = fmaxf(m_run, mx_cur);
+    // Raising the reference: this sub-step's exponentials use the new one at once; the
+    // accumulators are rescaled only after PV of the previous sub-step (old reference) is in.
+    const bool raised = __any(mx_cur > m_ref + slack);
+    float alpha = 1.f;
+    if (raised) {
+      const float m_new = fmaxf(m_run, __shfl_xor(m_run, 32, 64));
+      alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);   // 0 the first time
+      l_run *= alpha;
+      m_ref = m_new;
+    }
+    const float mc = m_ref * c;
+    bf16x8 f[16];
+#pragma unroll
+    for (int i = 0; i < IL_LEAD; ++i) f[i] = pre[i];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s_next[v] = 0.f;
+    unsigned u[8];
+    float ps = 0.f, mxn = 0.f;
+    IL_FENCE();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      // ---- matrix instruction of slot i
+      if (i < 8) s_next = MFMA(f[i], qf[i], s_next);
+      else oacc[(i - 8) & 3] = MFMA(f[i], p_prev[(i - 8) >> 2], oacc[(i - 8) & 3]);
+      // ---- fragment request IL_LEAD slots ahead
+      if (i + IL_LEAD < 8) {
+        f[i + IL_LEAD] = lds_frag3(kq + 16 * (i + IL_LEAD));
+      } else if (i + IL_LEAD < 16) {
+        const int sl = i + IL_LEAD - 8;
+        const lds_ptr ap = vq + 16 * (sl >> 2) * VSTR + 32 * (sl & 3);
+        f[i + IL_LEAD] = read_vt3(ap, ap + 8 * VSTR);
+      }
+      // ---- vector work in the shadow
+      if (i < 8) {
+        s_cur[2 * i] = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i], c, -mc));
+        s_cur[2 * i + 1] = __builtin_amdgcn_exp2f(fmaf(s_cur[2 * i + 1], c, -mc));
+        if (!FAST) {
+          if (8 * ((2 * i) >> 2) + 4 * g + ((2 * i) & 3) >= n_valid) s_cur[2 * i] = 0.f;
+          if (8 * ((2 * i + 1) >> 2) + 4 * g + ((2 * i + 1) & 3) >= n_valid) s_cur[2 * i + 1] = 0.f;
+        }
+      } else if (i < 12) {
+        const int b4 = 4 * (i - 8);
+        ps += (s_cur[b4] + s_cur[b4 + 1]) + (s_cur[b4 + 2] + s_cur[b4 + 3]);
+        u[2 * (i - 8)] = pack_bf16(s_cur[b4], s_cur[b4 + 1]);
+        u[2 * (i - 8) + 1] = pack_bf16(s_cur[b4 + 2], s_cur[b4 + 3]);
+      } else {
+        const int b4 = 4 * (i - 12);
+        const float m4 = max3(s_next[b4], s_next[b4 + 1], fmaxf(s_next[b4 + 2], s_next[b4 + 3]));
+        mxn = (i == 12) ? m4 : fmaxf(mxn, m4);
+      }
+      IL_FENCE();
+    }
+    if (raised) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[d][v] *= alpha;
+    }
+    l_run += ps;
+    p_prev[0] = __builtin_bit_cast(bf16x8, make_uint4(u[0], u[1], u[2], u[3]));
+    p_prev[1] = __builtin_bit_cast(bf16x8, make_uint4(u[4], u[5], u[6], u[7]));
+    mx_cur = mxn;
+#undef IL_FENCE
+  };
+  auto request_pre = [&](lds_ptr kn) {
+#pragma unroll
+    for (int i = 0; i < IL_LEAD; ++i) pre[i] = lds_frag3(kn + 16 * i);
+  };
+
+  for (int it = 0; it < n_blocks; ++it) {
+    const int n_valid = min(BN, clen - cpos);
+    cpos += BN;
+    if (cpos >= clen) {
+      ++cr;
+      cpos = 0;
+      if (cr < w.n_runs) clen = run_len(cr);
+    }
+    const int b_prev = (it + IL_BUFS - 1) % IL_BUFS, b_cur = it % IL_BUFS, b_next = (it + 1) % IL_BUFS;
+    // ---- sub-step 2 it: QK of keys [32, 64) of this stage, PV of the previous stage's keys [32, 64)
+    {
+      const lds_ptr kq = opaque(k_rd + b_cur * STAGE_ELEMS + 32 * LSTR);
+      const lds_ptr vq = opaque(it ? v_rd + b_prev * STAGE_ELEMS + 32 * VSTR : v_rd);   // it = 0: P is zero, any finite V
+      if (n_valid >= 32) substep(std::true_type{}, s_even, s_odd, kq, vq, 32);
+      else substep(std::false_type{}, s_even, s_odd, kq, vq, n_valid);
+    }
+    // publish the next stage, request the one after
+    if (it + 1 < n_blocks) { STAGE(b_next) }
+    __syncthreads();
+    if (it + 2 < n_blocks) { FETCH_NEXT() }
+    const lds_ptr k_next = opaque(k_rd + b_next * STAGE_ELEMS);
+    request_pre(k_next);
+    // ---- sub-step 2 it + 1: QK of keys [0, 32) of the next stage, PV of this stage's keys [0, 32)
+    {
+      const lds_ptr kq = k_next;
+      const lds_ptr vq = opaque(v_rd + b_cur * STAGE_ELEMS);
+      if (n_valid >= 64) substep(std::true_type{}, s_odd, s_even, kq, vq, 32);
+      else substep(std::false_type{}, s_odd, s_even, kq, vq, n_valid - 32);
+    }
+    request_pre(k_next + 32 * LSTR);
+  }
+#undef FETCH_NEXT
+  // ---- PV of the last sub-step: keys [32, 64) of the last stage
+  {
+    const lds_ptr vq = opaque(v_rd + ((n_blocks - 1) % IL_BUFS) * STAGE_ELEMS + 32 * VSTR);
+#pragma unroll
+    for (int sl = 0; sl < 8; ++sl) {
+      const lds_ptr ap = vq + 16 * (sl >> 2) * VSTR + 32 * (sl & 3);
+      oacc[sl & 3] = MFMA(read_vt3(ap, ap + 8 * VSTR), p_prev[sl >> 2], oacc[sl & 3]);
+    }
+  }
+  __syncthreads();
+
+  // ---- epilogue: normalise, transpose through LDS, store whole rows
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.f / l_tot;
+  uint16_t* st = smem + wave * 32 * LSTR;
+  STORE_TILE(0, oacc[0]) STORE_TILE(1, oacc[1]) STORE_TILE(2, oacc[2]) STORE_TILE(3, oacc[3])
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = (lane >> 4) + 4 * i;
+    if (32 * wave + row < w.n_rows)
+      *(uint4*)(O + (unsigned)(w.row0 + 32 * wave + row) * row_stride + (lane & 15) * 8) =
+          *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+  }
+}
+
 static int g_long_variant = getenv("VORTA_LONG_VARIANT") ? atoi(getenv("VORTA_LONG_VARIANT")) : 0;   // experiment switch
 
 static int set_lds_limit(const void* kernel, const char* name) {
@@ -813,6 +1054,10 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
       hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_pp_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, PP_LDS_BYTES);
       if (e != hipSuccess) attr_rc = fail(VORTA_EHIP, "hipFuncSetAttribute(attn_bf16_pp_kernel): %s", hipGetErrorString(e));
     }
+    if (!attr_rc) {
+      hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_il_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, IL_LDS_BYTES);
+      if (e != hipSuccess) attr_rc = fail(VORTA_EHIP, "hipFuncSetAttribute(attn_bf16_il_kernel): %s", hipGetErrorString(e));
+    }
   });
   if (attr_rc) return attr_rc;
   // dense + core-set heads: 256-row workgroups; window heads: 128-row workgroups (one tile each)
@@ -826,6 +1071,8 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
       hipLaunchKernelGGL(attn_bf16_m64_kernel, dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
     else if (g_long_variant == 2)
       hipLaunchKernelGGL(attn_bf16_pp_kernel, dim3(a.end_text), dim3(512), PP_LDS_BYTES, (hipStream_t)stream, a);
+    else if (g_long_variant == 3)
+      hipLaunchKernelGGL(attn_bf16_il_kernel, dim3(a.end_text), dim3(512), IL_LDS_BYTES, (hipStream_t)stream, a);
     else
       hipLaunchKernelGGL(attn_bf16_kernel<8>, dim3(a.end_text), dim3(512), LDS_BYTES, (hipStream_t)stream, a);
   }
