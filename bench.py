@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--workload", default="wan720p")
     ap.add_argument("--layout", type=int, default=1, help="1 = [heads][N][d], 0 = [N][heads][d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)")
@@ -111,6 +113,12 @@ def main():
     def step():
         vorta.vorta_routed_attention_layer(plan, q, k, v, routes, out=out, workspace=ws)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

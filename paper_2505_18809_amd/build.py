@@ -11,6 +11,9 @@ SOURCES = ["vorta_host.cpp", "vorta_passes.hip", "vorta_attn_f32.hip", "vorta_at
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # matrix instructions write their results to ordinary vector registers, which the softmax
+    # reads directly, also in the kernel that runs one wavefront per SIMD
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

@@ -13,6 +13,7 @@
 // Softmax statistics are fp32, exp via v_exp_f32 on scores pre-multiplied by log2(e).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
 
 #include "vorta_attn_common.h"
 
@@ -97,11 +98,26 @@ __device__ __forceinline__ lds_ptr opaque(lds_ptr p) {
 
 #define MFMA(a_, b_, c_) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b_, c_, 0, 0, 0)
 
+#ifdef VORTA_DEBUG_CLOCKS
+__device__ long long g_dbg_clk[4];
+__device__ unsigned g_dbg_stamps[18];
+#define DBG_CLK_BEGIN const long long dbg_c0 = __builtin_amdgcn_s_memtime(), dbg_r0 = __builtin_amdgcn_s_memrealtime();
+#define DBG_CLK_END(cond_)                                              \
+  if ((cond_) && blockIdx.x == 300 && threadIdx.x == 0) {                \
+    g_dbg_clk[0] = __builtin_amdgcn_s_memtime() - dbg_c0;                \
+    g_dbg_clk[1] = __builtin_amdgcn_s_memrealtime() - dbg_r0;            \
+    g_dbg_clk[2] = n_blocks;                                             \
+  }
+#else
+#define DBG_CLK_BEGIN
+#define DBG_CLK_END(cond_)
+#endif
+
 template <int NW>   // wavefronts per workgroup: 4 (two workgroups per CU) or 8 (one)
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   constexpr int STG_ROWS = 4 * NW, STG_PASSES = BN / STG_ROWS;   // staging: rows per pass, passes per block
-  const WorkItem w = decode_item<32 * NW, D>(a, blockIdx.x);
+  const WorkItem w = decode_item<32 * NW, D>(a, xcd_item(blockIdx.x, gridDim.x, NW == 4));
   const uint16_t* Q = (const uint16_t*)(w.seg == 0 ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
   const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
   const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
@@ -110,6 +126,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
+  DBG_CLK_BEGIN
 
   // Q^T fragments: lane = query (l32), 8 consecutive dims per 16-wide k slice
   bf16x8 qf[8];
@@ -310,6 +327,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
     r = nr; pos = npos; start = nstart; len = nlen;
   }
 
+  DBG_CLK_END(NW == 8)
   // ---- epilogue: normalise, transpose through LDS, store whole rows
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.f / l_tot;
@@ -332,9 +350,361 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   }
 }
 
-static int set_lds_limit(const void* kernel, const char* name) {
-  hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-  if (e != hipSuccess) return fail(VORTA_EHIP, "hipFuncSetAttribute(%s, %d B LDS): %s", name, LDS_BYTES, hipGetErrorString(e));
+
+// ------------------------------------------------------------------------------------------
+// Software-pipelined kernel for the dense and core-set segments (8 wavefronts, 256 query
+// rows, one workgroup per CU).  Every matrix instruction gets independent vector work to run
+// in its shadow, inside the same wavefront:
+//
+//   iteration i:   matrix pipe   O^T += V^T(i-1) P^T(i-1)   then   S^T(i+1) = K(i+1) Q^T
+//                  vector pipe   online softmax of S^T(i) -> P^T(i)   (independent of both)
+//                  memory        block i+2: registers -> LDS,   block i+3: global -> registers
+//
+// The iteration is written as 32 slots, one matrix instruction each, separated by scheduling
+// fences: a slot also requests the LDS fragments of the matrix instruction LEAD slots later
+// and carries a few instructions of the softmax (or of the staging).  The accumulators O^T
+// are rescaled to the new row maxima at the END of iteration i (rarely taken branch), after
+// P(i-1) V(i-1) went in and before P(i) V(i) does.  K/V blocks live in a ring of four LDS
+// stages: V(i-1) and K(i+1) are being read, block i waits for its second product, block i+2
+// is being written; one barrier per iteration.  Score tiles and probability fragments
+// alternate between two register sets from one iteration to the next, so nothing is copied.
+// ------------------------------------------------------------------------------------------
+namespace {
+constexpr int PIPE_BUFS = 4;
+constexpr int PIPE_LDS_BYTES = PIPE_BUFS * STAGE_ELEMS * 2;
+#ifndef PIPE_LEAD
+#define PIPE_LEAD 4
+#endif
+constexpr int LEAD = PIPE_LEAD;          // slots between a fragment request and its use
+}  // namespace
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x4* lds_u4_wptr;
+
+__global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  constexpr int STG_ROWS = 32;
+  const WorkItem w = decode_item<BM_LONG, D>(a, blockIdx.x);
+  const uint16_t* Q = (const uint16_t*)(w.seg == 0 ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
+  const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
+  const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
+  uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
+  const unsigned row_stride = (unsigned)w.row_stride;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l32 = lane & 31, g = lane >> 5;
+  DBG_CLK_BEGIN
+
+  bf16x8 qf[8];
+  {
+    const unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    const uint16_t* qp = Q + qrow * row_stride + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * ks));
+  }
+
+  auto run_start = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r]) : 0; };
+  auto run_len = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r + 1]) : w.single_len; };
+  int n_blocks = 0;
+  for (int r = 0; r < w.n_runs; ++r) n_blocks += (run_len(r) + BN - 1) / BN;
+
+  // ---- global -> register -> LDS staging: thread moves the 16-byte chunk (tid & 15) of rows
+  // (tid >> 4) and (tid >> 4) + 32 of K and of V.  The fetch stream walks the run list one
+  // block per call and stays on the last block once it is past the end (those extra copies
+  // land in ring stages nobody reads), so neither the loads nor the LDS writes need a guard.
+  const int ld_row = tid >> 4, ld_col = (tid & 15) * 8;
+  int fr = 0, fpos = 0, fstart = run_start(0), flen = run_len(0);
+  u32x4 kr0, kr1, vr0, vr1;
+  unsigned f_row0 = 0, f_lim = 0;
+  auto fetch_cursor = [&]() {      // first row and last valid row offset of the block, then advance
+    f_row0 = (unsigned)(fstart + fpos);
+    f_lim = (unsigned)(flen - 1 - fpos);
+    if (fpos + BN < flen) {
+      fpos += BN;
+    } else if (fr + 1 < w.n_runs) {
+      ++fr;
+      fpos = 0;
+      fstart = run_start(fr);
+      flen = run_len(fr);
+    }
+  };
+  auto row_off = [&](int i) {      // element offset of this thread's chunk in staging row i
+    return __umul24(f_row0 + min((unsigned)(ld_row + STG_ROWS * i), f_lim), row_stride) + (unsigned)ld_col;
+  };
+  auto ld16 = [&](const uint16_t* base, unsigned off) { return *(const u32x4*)(base + off); };
+  const lds_u4_wptr k_wr = (lds_u4_wptr)(smem + ld_row * LSTR + ld_col);
+  const lds_u4_wptr v_wr = (lds_u4_wptr)(smem + KTILE + ld_row * VSTR + ld_col);
+  auto stage_all = [&](int buf) {
+    k_wr[(buf * STAGE_ELEMS) / 8] = kr0;
+    k_wr[(buf * STAGE_ELEMS + STG_ROWS * LSTR) / 8] = kr1;
+    v_wr[(buf * STAGE_ELEMS) / 8] = vr0;
+    v_wr[(buf * STAGE_ELEMS + STG_ROWS * VSTR) / 8] = vr1;
+  };
+  auto fetch_all = [&]() {
+    fetch_cursor();
+    const unsigned o0_ = row_off(0), o1_ = row_off(1);
+    kr0 = ld16(K, o0_); vr0 = ld16(V, o0_);
+    kr1 = ld16(K, o1_); vr1 = ld16(V, o1_);
+  };
+  // valid keys of the blocks in compute order
+  int cr = 0, cpos = 0, clen = flen;
+  auto next_valid = [&]() {
+    const int nv = min(BN, clen - cpos);
+    if (cpos + BN < clen) {
+      cpos += BN;
+    } else if (cr + 1 < w.n_runs) {
+      ++cr;
+      cpos = 0;
+      clen = run_len(cr);
+    }
+    return nv;
+  };
+
+  fetch_all();
+  stage_all(0);
+  fetch_all();
+  stage_all(1);
+  fetch_all();                     // block 2 waits in registers for iteration 0
+  __syncthreads();
+
+  const lds_ptr k_rd = (lds_ptr)(smem + l32 * LSTR + 8 * g);
+  const int t16 = lane & 15, blk = lane >> 4;
+  const lds_ptr v_rd = (lds_ptr)(smem + KTILE + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3));
+
+  f32x16 o[4], sa0, sa1, sb0, sb1;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    o[0][v] = 0.f; o[1][v] = 0.f; o[2][v] = 0.f; o[3][v] = 0.f;
+    sa0[v] = 0.f; sa1[v] = 0.f; sb0[v] = 0.f; sb1[v] = 0.f;
+  }
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c = a.scale * 1.4426950408889634f;
+  bf16x8 pa[4], pb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) pa[i] = pb[i] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+
+  // element v of a 32-key score tile is key 8 (v >> 2) + 4 g + (v & 3)
+  auto mask_tail = [&](f32x16& t0, f32x16& t1, int n_valid) {
+    const int nv0 = n_valid - 4 * g, nv1 = nv0 - 32;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if (8 * (v >> 2) + (v & 3) >= nv0) t0[v] = -INFINITY;
+      if (8 * (v >> 2) + (v & 3) >= nv1) t1[v] = -INFINITY;
+    }
+  };
+
+  // scores of block 0
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    sa0 = MFMA(lds_frag3(k_rd + 16 * ks), qf[ks], sa0);
+    sa1 = MFMA(lds_frag3(k_rd + 32 * LSTR + 16 * ks), qf[ks], sa1);
+  }
+  {
+    const int nv = next_valid();
+    if (nv < BN) mask_tail(sa0, sa1, nv);
+  }
+
+#define SLOT_FENCE() __builtin_amdgcn_sched_barrier(0)
+  // first V^T fragments of the coming iteration, requested before the barrier of this one
+  bf16x8 vpre[LEAD];
+  auto v_frag = [&](lds_ptr vq, int n) {
+    const lds_ptr ap = vq + 16 * (n >> 2) * VSTR + 32 * (n & 3);
+    return read_vt3(ap, ap + 8 * VSTR);
+  };
+#pragma unroll
+  for (int n = 0; n < LEAD; ++n) vpre[n] = v_frag(v_rd, n);       // iteration 0 multiplies stage 0 by P = 0
+#ifdef PIPE_STAMPS
+  unsigned stamp_acc[6] = {0, 0, 0, 0, 0, 0};
+#endif
+  // One iteration.  sc*: scores of block i (in), sn*: scores of block i+1 (out),
+  // pp: P^T(i-1) (in), pc: P^T(i) (out).
+  auto body = [&](int i, f32x16& sc0, f32x16& sc1, f32x16& sn0, f32x16& sn1, bf16x8 (&pp)[4], bf16x8 (&pc)[4],
+                  auto last_tag) {
+    constexpr bool LAST = decltype(last_tag)::value;
+    const lds_ptr vq = opaque(v_rd + ((i ? i - 1 : 0) & 3) * STAGE_ELEMS);
+    const lds_ptr kq = opaque(k_rd + ((i + 1) & 3) * STAGE_ELEMS);
+    const int wbuf = (i + 2) & 3;
+    fetch_cursor();                                  // block i+3 (scalar work and branches: before the slots)
+    bf16x8 vf[16], kf[16];
+    auto v_req = [&](int n) { vf[n] = v_frag(vq, n); };
+    auto k_req = [&](int n) { kf[n] = lds_frag3(kq + 32 * (n & 1) * LSTR + 16 * (n >> 1)); };
+#ifdef PIPE_STAMPS
+    unsigned long long ts0, ts1, ts2, ts3, ts4, ts5;
+    asm volatile("s_memtime %0" : "=s"(ts0));
+#endif
+    const lds_ptr vq_next = opaque(v_rd + (i & 3) * STAGE_ELEMS);     // V(i): second product of iteration i+1
+#pragma unroll
+    for (int n = 0; n < LEAD; ++n) vf[n] = vpre[n];
+    float mxa = 0.f, mxb = 0.f, alpha = 0.f, mc = 0.f, ps0 = 0.f, ps1 = 0.f;
+    float xs[2][2], ex[2][2];
+    bool moved = false;
+    unsigned u[2][8];
+    unsigned off0 = 0, off1 = 0;
+#pragma unroll
+    for (int n = 0; n < 32; ++n) {
+      SLOT_FENCE();
+#ifdef PIPE_STAMPS
+      if (n == 1) asm volatile("s_memtime %0" : "=s"(ts1));
+      if (n == 8) asm volatile("s_memtime %0" : "=s"(ts2));
+      if (n == 16) asm volatile("s_memtime %0" : "=s"(ts3));
+      if (n == 24) asm volatile("s_memtime %0" : "=s"(ts4));
+#endif
+      // ---- matrix instruction of the slot
+      if (n < 16) {
+        o[n & 3] = MFMA(vf[n], pp[n >> 2], o[n & 3]);
+      } else if (!LAST) {
+        const int m = n - 16;
+        if (m == 0) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sn0[v] = 0.f;
+        }
+        if (m == 1) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sn1[v] = 0.f;
+        }
+        if (m & 1) sn1 = MFMA(kf[m], qf[m >> 1], sn1);
+        else sn0 = MFMA(kf[m], qf[m >> 1], sn0);
+      }
+      // ---- fragment requests for the slot LEAD ahead
+      if (n + LEAD < 16) v_req(n + LEAD);
+      else if (n + LEAD < 32 && !LAST) k_req(n + LEAD - 16);
+      else if (n + LEAD >= 32) vpre[n + LEAD - 32] = v_frag(vq_next, n + LEAD - 32);
+      // ---- vector work in the shadow of the matrix instruction.  The instructions of one slot
+      // do not depend on each other (a wavefront issues in order, so a dependent instruction
+      // would stall everything behind it for the latency of its producer): the row maximum
+      // runs as two interleaved chains, and the probability stream is staggered by stage --
+      // slot n scales pair n-5, exponentiates pair n-6, packs pair n-7 and sums pair n-8.
+      if (n < 4) {
+#pragma unroll
+        for (int k = 2 * n; k < 2 * n + 2; ++k) {     // links 0..7 of both chains
+          if (k == 0) { mxa = max3(sc0[0], sc0[1], sc0[2]); mxb = max3(sc1[0], sc1[1], sc1[2]); }
+          else if (k < 7) { mxa = max3(mxa, sc0[2 * k + 1], sc0[2 * k + 2]); mxb = max3(mxb, sc1[2 * k + 1], sc1[2 * k + 2]); }
+          else { mxa = fmaxf(mxa, sc0[15]); mxb = fmaxf(mxb, sc1[15]); }
+        }
+      } else if (n == 4) {
+        const float mx = max_xor32(fmaxf(mxa, mxb));
+        const float m_new = fmaxf(m_run, mx);
+        moved = m_new > m_run;
+        alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        m_run = m_new;
+        mc = m_new * c;
+      }
+      if (n >= 8 && n < 24) {                        // stage D: row sums from the rounded pairs
+        const int p = n - 8;
+        if (p >> 3) ps1 = pair_sum(u[1][p & 7], ps1);
+        else ps0 = pair_sum(u[0][p & 7], ps0);
+      }
+      if (n >= 7 && n < 23) {                        // stage C: pack to bf16
+        const int p = n - 7;
+        u[p >> 3][p & 7] = pack_bf16(ex[p & 1][0], ex[p & 1][1]);
+        asm volatile("" : "+v"(u[p >> 3][p & 7]));   // used next iteration: keep its computation in this slot
+      }
+      if (n >= 6 && n < 22) {                        // stage B: exponentials
+        const int p = n - 6;
+        ex[p & 1][0] = __builtin_amdgcn_exp2f(xs[p & 1][0]);
+        ex[p & 1][1] = __builtin_amdgcn_exp2f(xs[p & 1][1]);
+      }
+      if (n >= 5 && n < 21) {                        // stage A: scale and subtract the maximum
+        const int p = n - 5, t = p >> 3, wi = p & 7;
+        xs[p & 1][0] = fmaf(t ? sc1[2 * wi] : sc0[2 * wi], c, -mc);
+        xs[p & 1][1] = fmaf(t ? sc1[2 * wi + 1] : sc0[2 * wi + 1], c, -mc);
+      }
+      if (n == 24) {
+        l_run = fmaf(l_run, alpha, ps0 + ps1);
+        asm volatile("" : "+v"(l_run));
+      } else if (n == 22) {                          // block i+3: addresses, then one load per slot
+        off0 = row_off(0);
+        off1 = row_off(1);
+      }
+      // ---- staging: block i+2 leaves the registers (slots 12-15), block i+3 enters (23-26)
+      if (n == 12) k_wr[(wbuf * STAGE_ELEMS) / 8] = kr0;
+      if (n == 13) k_wr[(wbuf * STAGE_ELEMS + STG_ROWS * LSTR) / 8] = kr1;
+      if (n == 14) v_wr[(wbuf * STAGE_ELEMS) / 8] = vr0;
+      if (n == 15) v_wr[(wbuf * STAGE_ELEMS + STG_ROWS * VSTR) / 8] = vr1;
+      if (n == 23) kr0 = ld16(K, off0);
+      if (n == 24) vr0 = ld16(V, off0);
+      if (n == 25) kr1 = ld16(K, off1);
+      if (n == 26) vr1 = ld16(V, off1);
+    }
+    SLOT_FENCE();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      pc[h] = __builtin_bit_cast(bf16x8, make_uint4(u[0][4 * h], u[0][4 * h + 1], u[0][4 * h + 2], u[0][4 * h + 3]));
+      pc[2 + h] = __builtin_bit_cast(bf16x8, make_uint4(u[1][4 * h], u[1][4 * h + 1], u[1][4 * h + 2], u[1][4 * h + 3]));
+    }
+#ifdef PIPE_STAMPS
+    asm volatile("s_memtime %0" : "=s"(ts5));
+#endif
+    __syncthreads();
+#ifdef PIPE_STAMPS
+    {
+      unsigned long long ts6;
+      asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts6));
+      stamp_acc[0] += (unsigned)(ts1 - ts0); stamp_acc[1] += (unsigned)(ts2 - ts1); stamp_acc[2] += (unsigned)(ts3 - ts2);
+      stamp_acc[3] += (unsigned)(ts4 - ts3); stamp_acc[4] += (unsigned)(ts5 - ts4); stamp_acc[5] += (unsigned)(ts6 - ts5);
+    }
+#endif
+    // ---- bring the accumulators to the new maxima before P(i) V(i) is added to them
+    if (__any(moved)) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[d][v] *= alpha;
+    }
+    if constexpr (!LAST) {
+      const int nv = next_valid();
+      if (nv < BN) mask_tail(sn0, sn1, nv);
+    }
+  };
+  {
+    int i = 0;
+    for (; i + 2 < n_blocks; i += 2) {
+      body(i, sa0, sa1, sb0, sb1, pa, pb, std::false_type{});
+      body(i + 1, sb0, sb1, sa0, sa1, pb, pa, std::false_type{});
+    }
+    if (i + 2 == n_blocks) {
+      body(i, sa0, sa1, sb0, sb1, pa, pb, std::false_type{});
+      body(i + 1, sb0, sb1, sa0, sa1, pb, pa, std::true_type{});
+    } else {
+      body(i, sa0, sa1, sb0, sb1, pa, pb, std::true_type{});
+#pragma unroll
+      for (int k = 0; k < 4; ++k) pa[k] = pb[k];
+    }
+  }
+#undef SLOT_FENCE
+
+  // ---- second product of the last block (its probabilities are in pa)
+  {
+    const lds_ptr vq = opaque(v_rd + ((n_blocks - 1) & 3) * STAGE_ELEMS);
+#pragma unroll
+    for (int n = 0; n < 16; ++n)
+      o[n & 3] = MFMA(n < LEAD ? vpre[n] : v_frag(vq, n), pa[n >> 2], o[n & 3]);
+  }
+  DBG_CLK_END(true)
+#ifdef PIPE_STAMPS
+  if (blockIdx.x == 300 && lane == 0 && (wave == 0 || wave == 4 || wave == 7))
+    for (int k = 0; k < 6; ++k) g_dbg_stamps[(wave == 0 ? 0 : wave == 4 ? 1 : 2) * 6 + k] = stamp_acc[k];
+#endif
+  __syncthreads();   // every wavefront is done with the ring before stage 0 is reused below
+
+  // ---- epilogue: normalise, transpose through LDS, store whole rows
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.f / l_tot;
+  uint16_t* st = smem + wave * 32 * LSTR;
+  STORE_TILE(0, o[0]) STORE_TILE(1, o[1]) STORE_TILE(2, o[2]) STORE_TILE(3, o[3])
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = (lane >> 4) + 4 * i;
+    if (32 * wave + row < w.n_rows)
+      *(uint4*)(O + (unsigned)(w.row0 + 32 * wave + row) * row_stride + (lane & 15) * 8) =
+          *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+  }
+}
+
+static int set_lds_limit(const void* kernel, const char* name, int bytes) {
+  hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return fail(VORTA_EHIP, "hipFuncSetAttribute(%s, %d B LDS): %s", name, bytes, hipGetErrorString(e));
   return VORTA_OK;
 }
 
@@ -342,17 +712,19 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   static std::once_flag once;
   static int attr_rc = VORTA_OK;
   std::call_once(once, [] {
-    attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4>, "attn_bf16_kernel<4>");
-    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_kernel<8>, "attn_bf16_kernel<8>");
+    attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4>, "attn_bf16_kernel<4>", LDS_BYTES);
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel, "attn_bf16_pipe_kernel", PIPE_LDS_BYTES);
   });
   if (attr_rc) return attr_rc;
-  // dense + core-set heads: 256-row workgroups; window heads: 128-row workgroups (one tile each)
+  // dense + core-set heads: pipelined kernel, 256-row workgroups; window heads: one 128-row
+  // workgroup per tile
   RouteLists long_rl = rl, win_rl = rl;
   long_rl.count[1] = 0;
   win_rl.count[0] = win_rl.count[2] = 0;
   AttnArgs a;
   if (int rc = fill_attn_args(p, long_rl, io, BM_LONG, &a)) return rc;
-  if (a.end_text > 0) hipLaunchKernelGGL(attn_bf16_kernel<8>, dim3(a.end_text), dim3(512), LDS_BYTES, (hipStream_t)stream, a);
+  if (a.end_text > 0)
+    hipLaunchKernelGGL(attn_bf16_pipe_kernel, dim3(a.end_text), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
   if (int rc = fill_attn_args(p, win_rl, io, BM, &a)) return rc;
   if (a.end_text > 0) hipLaunchKernelGGL(attn_bf16_kernel<4>, dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
   hipError_t e = hipGetLastError();
@@ -362,3 +734,11 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
 
 }  // namespace vorta
 
+#ifdef VORTA_DEBUG_CLOCKS
+extern "C" int vorta_debug_stamps(unsigned* out18) {
+  return hipMemcpyFromSymbol(out18, HIP_SYMBOL(vorta::g_dbg_stamps), sizeof(unsigned) * 18) == hipSuccess ? 0 : -6;
+}
+extern "C" int vorta_debug_clocks(long long* out4) {
+  return hipMemcpyFromSymbol(out4, HIP_SYMBOL(vorta::g_dbg_clk), sizeof(long long) * 4) == hipSuccess ? 0 : -6;
+}
+#endif

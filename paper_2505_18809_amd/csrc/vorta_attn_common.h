@@ -95,6 +95,18 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
   return w;
 }
 
+// Work item of a workgroup.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs
+// (each with its own L2); with chunked = true the ids are re-dealt so that every XCD gets one
+// contiguous range of the n items instead -- neighbouring window tiles, whose key sets
+// overlap, then run on the same XCD at about the same time and share its L2.  Only for
+// launches whose items all cost the same (a contiguous deal of unequal items would leave
+// some XCDs with all the long ones).
+__device__ __forceinline__ int xcd_item(int block, int n, bool chunked) {
+  if (!chunked) return block;
+  const int xcd = block & 7, loc = block >> 3, q = n >> 3, r = n & 7;
+  return xcd * q + min(xcd, r) + loc;
+}
+
 // Fills everything of AttnArgs that does not depend on the kernel's block size.
 int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, AttnArgs* a);
 
