@@ -373,13 +373,16 @@ namespace {
 constexpr int PIPE_BUFS = 4;
 constexpr int PIPE_LDS_BYTES = PIPE_BUFS * STAGE_ELEMS * 2;
 #ifndef PIPE_LEAD
-#define PIPE_LEAD 4
+#define PIPE_LEAD 2
 #endif
 constexpr int LEAD = PIPE_LEAD;          // slots between a fragment request and its use
+constexpr float P_MAX = 256.f;           // largest probability (relative to the row reference) the fast path accepts
 }  // namespace
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) u32x4* lds_u4_wptr;
+
+__device__ __forceinline__ float elem_of(const f32x16& t0, const f32x16& t1, int e) { return e < 16 ? t0[e] : t1[e - 16]; }
 
 __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
@@ -477,7 +480,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     o[0][v] = 0.f; o[1][v] = 0.f; o[2][v] = 0.f; o[3][v] = 0.f;
     sa0[v] = 0.f; sa1[v] = 0.f; sb0[v] = 0.f; sb1[v] = 0.f;
   }
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_ref = -INFINITY, l_run = 0.f;   // row reference (a lagging running maximum) and row sum
   const float c = a.scale * 1.4426950408889634f;
   bf16x8 pa[4], pb[4];
 #pragma unroll
@@ -535,10 +538,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     const lds_ptr vq_next = opaque(v_rd + (i & 3) * STAGE_ELEMS);     // V(i): second product of iteration i+1
 #pragma unroll
     for (int n = 0; n < LEAD; ++n) vf[n] = vpre[n];
-    float mxa = 0.f, mxb = 0.f, alpha = 0.f, mc = 0.f, ps0 = 0.f, ps1 = 0.f;
-    float xs[2][2], ex[2][2];
-    bool moved = false;
+    float ps0 = 0.f, ps1 = 0.f;
+    float x[32], ex[32];
     unsigned u[2][8];
+    const float mc = m_ref * c;
     unsigned off0 = 0, off1 = 0;
 #pragma unroll
     for (int n = 0; n < 32; ++n) {
@@ -569,50 +572,28 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
       if (n + LEAD < 16) v_req(n + LEAD);
       else if (n + LEAD < 32 && !LAST) k_req(n + LEAD - 16);
       else if (n + LEAD >= 32) vpre[n + LEAD - 32] = v_frag(vq_next, n + LEAD - 32);
-      // ---- vector work in the shadow of the matrix instruction.  The instructions of one slot
-      // do not depend on each other (a wavefront issues in order, so a dependent instruction
-      // would stall everything behind it for the latency of its producer): the row maximum
-      // runs as two interleaved chains, and the probability stream is staggered by stage --
-      // slot n scales pair n-5, exponentiates pair n-6, packs pair n-7 and sums pair n-8.
-      if (n < 4) {
-#pragma unroll
-        for (int k = 2 * n; k < 2 * n + 2; ++k) {     // links 0..7 of both chains
-          if (k == 0) { mxa = max3(sc0[0], sc0[1], sc0[2]); mxb = max3(sc1[0], sc1[1], sc1[2]); }
-          else if (k < 7) { mxa = max3(mxa, sc0[2 * k + 1], sc0[2 * k + 2]); mxb = max3(mxb, sc1[2 * k + 1], sc1[2 * k + 2]); }
-          else { mxa = fmaxf(mxa, sc0[15]); mxb = fmaxf(mxb, sc1[15]); }
-        }
-      } else if (n == 4) {
-        const float mx = max_xor32(fmaxf(mxa, mxb));
-        const float m_new = fmaxf(m_run, mx);
-        moved = m_new > m_run;
-        alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-        m_run = m_new;
-        mc = m_new * c;
+      // ---- vector work in the shadow of the matrix instruction: the probabilities of block i
+      // relative to the row reference m_ref, spread evenly over the slots and staggered by
+      // stage so that no instruction of a slot waits for another one of the same slot (a
+      // wavefront issues in order): slot n scales element n+1, exponentiates element n-1,
+      // packs pair (n-3)/2 (odd n) and adds pair (n-4)/2 to the row sums (even n).
+      // Element e < 16 is sc0[e], element e >= 16 is sc1[e - 16]; pair p = elements 2p, 2p+1.
+      auto elem = [&](int e) { return e < 16 ? sc0[e] : sc1[e - 16]; };
+      if (n == 0) { x[0] = fmaf(elem(0), c, -mc); x[1] = fmaf(elem(1), c, -mc); }
+      if (n >= 1 && n <= 30) x[n + 1] = fmaf(elem(n + 1), c, -mc);
+      if (n >= 1 && n <= 30) ex[n - 1] = __builtin_amdgcn_exp2f(x[n - 1]);
+      if (n == 31) { ex[30] = __builtin_amdgcn_exp2f(x[30]); ex[31] = __builtin_amdgcn_exp2f(x[31]); }
+      if (n >= 3 && (n & 1)) {
+        const int p = (n - 3) >> 1;
+        u[p >> 3][p & 7] = pack_bf16(ex[2 * p], ex[2 * p + 1]);
+        asm volatile("" : "+v"(u[p >> 3][p & 7]));   // used next iteration: keep its computation in this slot
       }
-      if (n >= 8 && n < 24) {                        // stage D: row sums from the rounded pairs
-        const int p = n - 8;
+      if (n >= 4 && !(n & 1)) {
+        const int p = (n - 4) >> 1;
         if (p >> 3) ps1 = pair_sum(u[1][p & 7], ps1);
         else ps0 = pair_sum(u[0][p & 7], ps0);
       }
-      if (n >= 7 && n < 23) {                        // stage C: pack to bf16
-        const int p = n - 7;
-        u[p >> 3][p & 7] = pack_bf16(ex[p & 1][0], ex[p & 1][1]);
-        asm volatile("" : "+v"(u[p >> 3][p & 7]));   // used next iteration: keep its computation in this slot
-      }
-      if (n >= 6 && n < 22) {                        // stage B: exponentials
-        const int p = n - 6;
-        ex[p & 1][0] = __builtin_amdgcn_exp2f(xs[p & 1][0]);
-        ex[p & 1][1] = __builtin_amdgcn_exp2f(xs[p & 1][1]);
-      }
-      if (n >= 5 && n < 21) {                        // stage A: scale and subtract the maximum
-        const int p = n - 5, t = p >> 3, wi = p & 7;
-        xs[p & 1][0] = fmaf(t ? sc1[2 * wi] : sc0[2 * wi], c, -mc);
-        xs[p & 1][1] = fmaf(t ? sc1[2 * wi + 1] : sc0[2 * wi + 1], c, -mc);
-      }
-      if (n == 24) {
-        l_run = fmaf(l_run, alpha, ps0 + ps1);
-        asm volatile("" : "+v"(l_run));
-      } else if (n == 22) {                          // block i+3: addresses, then one load per slot
+      if (n == 22) {                                 // block i+3: addresses, then one load per slot
         off0 = row_off(0);
         off1 = row_off(1);
       }
@@ -627,11 +608,11 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
       if (n == 26) vr1 = ld16(V, off1);
     }
     SLOT_FENCE();
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      pc[h] = __builtin_bit_cast(bf16x8, make_uint4(u[0][4 * h], u[0][4 * h + 1], u[0][4 * h + 2], u[0][4 * h + 3]));
-      pc[2 + h] = __builtin_bit_cast(bf16x8, make_uint4(u[1][4 * h], u[1][4 * h + 1], u[1][4 * h + 2], u[1][4 * h + 3]));
-    }
+    u[1][7] = pack_bf16(ex[30], ex[31]);
+    ps1 = pair_sum(u[1][6], ps1);
+    ps1 = pair_sum(u[1][7], ps1);
+    float ps = ps0 + ps1;
+    asm volatile("" : "+v"(u[1][7]), "+v"(ps));
 #ifdef PIPE_STAMPS
     asm volatile("s_memtime %0" : "=s"(ts5));
 #endif
@@ -644,12 +625,39 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
       stamp_acc[3] += (unsigned)(ts4 - ts3); stamp_acc[4] += (unsigned)(ts5 - ts4); stamp_acc[5] += (unsigned)(ts6 - ts5);
     }
 #endif
-    // ---- bring the accumulators to the new maxima before P(i) V(i) is added to them
-    if (__any(moved)) {
+    // ---- reference check.  No probability exceeds its row sum, so ps <= P_MAX proves that no
+    // score of the block was more than log2(P_MAX) above the reference.  Otherwise (always for
+    // the first block, whose reference is -inf; afterwards only when a row maximum jumps) the
+    // block is redone against the true running maximum: new reference, accumulators and sum
+    // rescaled to it, probabilities recomputed from the scores, which are still in registers.
+    if (__any(!(ps <= P_MAX))) {
+      float mx = max3(sc0[0], sc1[0], sc0[1]);
+#pragma unroll
+      for (int k = 1; k < 15; ++k) mx = max3(mx, sc1[k], sc0[k + 1]);
+      mx = max_xor32(fmaxf(mx, sc1[15]));
+      const float m_new = fmaxf(m_ref, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);     // 0 for the first block
+      m_ref = m_new;
+      const float mc2 = m_new * c;
+      ps = 0.f;
+#pragma unroll
+      for (int p = 0; p < 16; ++p) {
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(elem_of(sc0, sc1, 2 * p), c, -mc2));
+        const float e1 = __builtin_amdgcn_exp2f(fmaf(elem_of(sc0, sc1, 2 * p + 1), c, -mc2));
+        u[p >> 3][p & 7] = pack_bf16(e0, e1);
+        ps = pair_sum(u[p >> 3][p & 7], ps);
+      }
+      l_run *= alpha;
 #pragma unroll
       for (int d = 0; d < 4; ++d)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[d][v] *= alpha;
+    }
+    l_run += ps;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      pc[h] = __builtin_bit_cast(bf16x8, make_uint4(u[0][4 * h], u[0][4 * h + 1], u[0][4 * h + 2], u[0][4 * h + 3]));
+      pc[2 + h] = __builtin_bit_cast(bf16x8, make_uint4(u[1][4 * h], u[1][4 * h + 1], u[1][4 * h + 2], u[1][4 * h + 3]));
     }
     if constexpr (!LAST) {
       const int nv = next_valid();
