@@ -450,9 +450,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     kr1 = ld16(K, o1_); vr1 = ld16(V, o1_);
   };
   // valid keys of the blocks in compute order
-  int cr = 0, cpos = 0, clen = flen;
-  auto next_valid = [&]() {
-    const int nv = min(BN, clen - cpos);
+  int cr = 0, cpos = 0, clen = flen, cblk = 0;
+  auto next_valid = [&]() {      // 0 past the last block: a block of masked keys adds nothing
+    const int nv = cblk < n_blocks ? min(BN, clen - cpos) : 0;
+    ++cblk;
     if (cpos + BN < clen) {
       cpos += BN;
     } else if (cr + 1 < w.n_runs) {
@@ -521,9 +522,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
 #endif
   // One iteration.  sc*: scores of block i (in), sn*: scores of block i+1 (out),
   // pp: P^T(i-1) (in), pc: P^T(i) (out).
-  auto body = [&](int i, f32x16& sc0, f32x16& sc1, f32x16& sn0, f32x16& sn1, bf16x8 (&pp)[4], bf16x8 (&pc)[4],
-                  auto last_tag) {
-    constexpr bool LAST = decltype(last_tag)::value;
+  auto body = [&](int i, f32x16& sc0, f32x16& sc1, f32x16& sn0, f32x16& sn1, bf16x8 (&pp)[4], bf16x8 (&pc)[4]) {
     const lds_ptr vq = opaque(v_rd + ((i ? i - 1 : 0) & 3) * STAGE_ELEMS);
     const lds_ptr kq = opaque(k_rd + ((i + 1) & 3) * STAGE_ELEMS);
     const int wbuf = (i + 2) & 3;
@@ -555,7 +554,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
       // ---- matrix instruction of the slot
       if (n < 16) {
         o[n & 3] = MFMA(vf[n], pp[n >> 2], o[n & 3]);
-      } else if (!LAST) {
+      } else {
         const int m = n - 16;
         if (m == 0) {
 #pragma unroll
@@ -570,8 +569,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
       }
       // ---- fragment requests for the slot LEAD ahead
       if (n + LEAD < 16) v_req(n + LEAD);
-      else if (n + LEAD < 32 && !LAST) k_req(n + LEAD - 16);
-      else if (n + LEAD >= 32) vpre[n + LEAD - 32] = v_frag(vq_next, n + LEAD - 32);
+      else if (n + LEAD < 32) k_req(n + LEAD - 16);
+      else vpre[n + LEAD - 32] = v_frag(vq_next, n + LEAD - 32);
       // ---- vector work in the shadow of the matrix instruction: the probabilities of block i
       // relative to the row reference m_ref, spread evenly over the slots and staggered by
       // stage so that no instruction of a slot waits for another one of the same slot (a
@@ -659,31 +658,23 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
       pc[h] = __builtin_bit_cast(bf16x8, make_uint4(u[0][4 * h], u[0][4 * h + 1], u[0][4 * h + 2], u[0][4 * h + 3]));
       pc[2 + h] = __builtin_bit_cast(bf16x8, make_uint4(u[1][4 * h], u[1][4 * h + 1], u[1][4 * h + 2], u[1][4 * h + 3]));
     }
-    if constexpr (!LAST) {
-      const int nv = next_valid();
-      if (nv < BN) mask_tail(sn0, sn1, nv);
-    }
+    const int nv = next_valid();
+    if (nv < BN) mask_tail(sn0, sn1, nv);
   };
-  {
-    int i = 0;
-    for (; i + 2 < n_blocks; i += 2) {
-      body(i, sa0, sa1, sb0, sb1, pa, pb, std::false_type{});
-      body(i + 1, sb0, sb1, sa0, sa1, pb, pa, std::false_type{});
-    }
-    if (i + 2 == n_blocks) {
-      body(i, sa0, sa1, sb0, sb1, pa, pb, std::false_type{});
-      body(i + 1, sb0, sb1, sa0, sa1, pb, pa, std::true_type{});
-    } else {
-      body(i, sa0, sa1, sb0, sb1, pa, pb, std::true_type{});
-#pragma unroll
-      for (int k = 0; k < 4; ++k) pa[k] = pb[k];
-    }
+  // An even number of iterations, so the two register sets swap back; when the block count
+  // is odd the last iteration works on a block of masked keys (probabilities 0) and only its
+  // second product, of the real last block, matters.  The scores an iteration computes for
+  // the block after the last one come from a ring stage holding a copy of the last block.
+  for (int i = 0; i < n_blocks; i += 2) {
+    body(i, sa0, sa1, sb0, sb1, pa, pb);
+    body(i + 1, sb0, sb1, sa0, sa1, pb, pa);
   }
 #undef SLOT_FENCE
 
-  // ---- second product of the last block (its probabilities are in pa)
+  // ---- second product of the last iteration's block (its probabilities are in pa)
   {
-    const lds_ptr vq = opaque(v_rd + ((n_blocks - 1) & 3) * STAGE_ELEMS);
+    const int last = ((n_blocks + 1) & ~1) - 1;
+    const lds_ptr vq = opaque(v_rd + (last & 3) * STAGE_ELEMS);
 #pragma unroll
     for (int n = 0; n < 16; ++n)
       o[n & 3] = MFMA(n < LEAD ? vpre[n] : v_frag(vq, n), pa[n >> 2], o[n & 3]);
