@@ -171,8 +171,7 @@ int launch_unpool(vorta_plan* p, const RouteLists& rl, const void* o_c, const in
 }
 
 // ------------------------------------------------------------------------------------------
-// Bucketed core-set selection.  One wavefront per (bucket, head): lanes split the feature
-// dimension, fp64 dot products are reduced across the wavefront, then lane j ranks token j.
+// Bucketed core-set selection (helpers; the kernels follow).
 // ------------------------------------------------------------------------------------------
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -186,12 +185,6 @@ template <> struct Elem<uint16_t> {   // bf16 bits
     *p = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
   }
 };
-
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
 
 struct Bucket {
   int f0, h0, w0;   // origin
@@ -219,44 +212,86 @@ __device__ __forceinline__ int bucket_token(const Geo& g, const Bucket& k, int j
   return ((k.f0 + a) * g.H + k.h0 + b) * g.W + k.w0 + c;
 }
 
-template <typename T, int DPL>   // DPL = head_dim / 64 feature elements per lane
+// 16-byte chunk of a row widened to fp64 (8 bf16 or 4 fp32 elements)
+template <typename T> struct Chunk;
+template <> struct Chunk<uint16_t> {
+  static constexpr int N = 8;
+  __device__ static void load(const uint16_t* p, double* x) {
+    const uint4 u = *(const uint4*)p;
+    const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = (double)__uint_as_float(w[i] << 16);
+      x[2 * i + 1] = (double)__uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+template <> struct Chunk<float> {
+  static constexpr int N = 4;
+  __device__ static void load(const float* p, double* x) {
+    const float4 u = *(const float4*)p;
+    x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w;
+  }
+};
+
+// sum over the 4 lanes of a quad (lanes 4k .. 4k+3)
+__device__ __forceinline__ double quad_sum(double v) {
+  v += __shfl_xor(v, 1, 64);
+  v += __shfl_xor(v, 2, 64);
+  return v;
+}
+
+// One wavefront per (bucket, head).  Four lanes share a token: lane 4t + q holds quarter q of
+// token t's feature row (16-byte loads, all rows of a pass in flight at once), so a pass of
+// the wavefront covers 16 tokens; partial dot products and norms are fp64 and are summed
+// over the quad.  Then lane j ranks token j.
+template <typename T, int D>   // D = head_dim
 __global__ __launch_bounds__(256) void bcs_index_kernel(const T* __restrict__ feat, HeadList hl, Geo g,
                                                         int n_buckets, const int* __restrict__ slot_base,
                                                         long head_stride, long row_stride, int Lc,
                                                         int* __restrict__ keep_idx, int* __restrict__ assign) {
 #pragma clang fp contract(off)
+  constexpr int EP = D / 4;                 // elements per lane
+  constexpr int CH = EP / Chunk<T>::N;      // 16-byte chunks per lane
   const int lane = threadIdx.x & 63;
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int s = blockIdx.y;
   if (b >= n_buckets) return;
   const Bucket k = bucket_of(g, b);
-  const T* base = feat + hl.id[s] * head_stride + lane * DPL;
+  const int quarter = lane & 3, tl = lane >> 2;
+  const T* base = feat + hl.id[s] * head_stride + quarter * EP;
 
-  double xc[DPL], nc = 0.0;
+  double xc[EP], nc = 0.0;
   {
     const T* row = base + (long)bucket_token(g, k, k.centre) * row_stride;
 #pragma unroll
-    for (int e = 0; e < DPL; ++e) { xc[e] = Elem<T>::load(row + e); nc += xc[e] * xc[e]; }
+    for (int ch = 0; ch < CH; ++ch) Chunk<T>::load(row + ch * Chunk<T>::N, xc + ch * Chunk<T>::N);
+#pragma unroll
+    for (int e = 0; e < EP; ++e) nc += xc[e] * xc[e];
   }
-  nc = wave_sum(nc);
+  nc = quad_sum(nc);
 
   double my_sim = 0.0;
-  for (int j = 0; j < k.size; ++j) {
-    if (j == k.centre) continue;
-    const T* row = base + (long)bucket_token(g, k, j) * row_stride;
-    double dot = 0.0, nj = 0.0;
+  for (int pass = 0; pass * 16 < k.size; ++pass) {
+    const int j = pass * 16 + tl;
+    const bool valid = j < k.size && j != k.centre;
+    const T* row = base + (long)bucket_token(g, k, valid ? j : k.centre) * row_stride;
+    double x[EP], dot = 0.0, nj = 0.0;
 #pragma unroll
-    for (int e = 0; e < DPL; ++e) {
-      const double x = Elem<T>::load(row + e);
-      dot += xc[e] * x;
-      nj += x * x;
+    for (int ch = 0; ch < CH; ++ch) Chunk<T>::load(row + ch * Chunk<T>::N, x + ch * Chunk<T>::N);
+#pragma unroll
+    for (int e = 0; e < EP; ++e) {
+      dot += xc[e] * x[e];
+      nj += x[e] * x[e];
     }
-    dot = wave_sum(dot);
-    nj = wave_sum(nj);
+    dot = quad_sum(dot);
+    nj = quad_sum(nj);
     double sim = 0.0;
-    if (nc != 0.0 && nj != 0.0) sim = dot / sqrt(nc * nj);
+    if (valid && nc != 0.0 && nj != 0.0) sim = dot / sqrt(nc * nj);
     if (!(sim == sim)) sim = 0.0;       // non-finite features: keep the ranking a total order
-    if (lane == j) my_sim = sim;
+    // token 16 pass + t sits in lanes 4t .. 4t+3; hand it to lane 16 pass + t
+    const double mine = __shfl(sim, 4 * (lane & 15), 64);
+    if ((lane >> 4) == pass) my_sim = mine;
   }
 
   // rank of token `lane` among the non-centre tokens: larger similarity first, ties by index
@@ -287,55 +322,78 @@ int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const void* feat, int3
   const Geo g = make_geo(p);
   hipStream_t st = (hipStream_t)stream;
   if (p->d.dtype == VORTA_BF16)
-    hipLaunchKernelGGL((bcs_index_kernel<uint16_t, 2>), grid, dim3(256), 0, st, (const uint16_t*)feat, hl, g,
+    hipLaunchKernelGGL((bcs_index_kernel<uint16_t, 128>), grid, dim3(256), 0, st, (const uint16_t*)feat, hl, g,
                        p->n_buckets, p->d_slot_base, ut.head_stride, ut.row_stride, (int)p->Lc, keep_idx, assign);
   else if (p->d.head_dim == 64)
-    hipLaunchKernelGGL((bcs_index_kernel<float, 1>), grid, dim3(256), 0, st, (const float*)feat, hl, g,
+    hipLaunchKernelGGL((bcs_index_kernel<float, 64>), grid, dim3(256), 0, st, (const float*)feat, hl, g,
                        p->n_buckets, p->d_slot_base, ut.head_stride, ut.row_stride, (int)p->Lc, keep_idx, assign);
   else
-    hipLaunchKernelGGL((bcs_index_kernel<float, 2>), grid, dim3(256), 0, st, (const float*)feat, hl, g,
+    hipLaunchKernelGGL((bcs_index_kernel<float, 128>), grid, dim3(256), 0, st, (const float*)feat, hl, g,
                        p->n_buckets, p->d_slot_base, ut.head_stride, ut.row_stride, (int)p->Lc, keep_idx, assign);
   return launch_status("bcs_index_kernel");
 }
 
 // ------------------------------------------------------------------------------------------
-// pool / merge: one wavefront per (bucket, head); a kept token's row is copied to its slot,
-// the centre's slot receives the mean of the centre and the tokens pruned into it.
+// pool / merge: one wavefront per (bucket, head).  A row is CPR 16-byte chunks; lane
+// (c = lane % CPR, group = lane / CPR) moves chunk c of the tokens group, group + G, ...
+// (G = 64 / CPR token groups).  A kept token's chunk is copied to its slot; the chunks of the
+// centre and of the tokens pruned into it are summed in fp64, the G partial sums are added
+// across the groups, and group 0 writes the mean to the centre's slot.
 // ------------------------------------------------------------------------------------------
-template <typename T, int DPL>
+template <typename T, int D>
 __global__ __launch_bounds__(256) void bcs_pool_kernel(const T* __restrict__ src, HeadList hl, Geo g,
                                                        int n_buckets, long head_stride, long row_stride,
-                                                       int Lc, int n_core_rows, int head_dim,
+                                                       int Lc, int n_core_rows,
                                                        const int* __restrict__ assign, T* __restrict__ dst) {
+  constexpr int CN = Chunk<T>::N;           // elements per chunk
+  constexpr int CPR = D / CN;               // chunks per row: 16 or 32
+  constexpr int G = 64 / CPR;               // token groups per pass
   const int lane = threadIdx.x & 63;
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int s = blockIdx.y;
   if (b >= n_buckets) return;
   const Bucket k = bucket_of(g, b);
-  const T* base = src + hl.id[s] * head_stride + lane * DPL;
-  T* out = dst + (long)s * n_core_rows * head_dim + lane * DPL;
+  const int c = lane % CPR, grp = lane / CPR;
+  const T* base = src + hl.id[s] * head_stride + c * CN;
+  T* out = dst + (long)s * n_core_rows * D + c * CN;
 
   int my_slot = 0;
   if (lane < k.size) my_slot = assign[(long)s * g.L + bucket_token(g, k, lane)];
   const int centre_slot = __shfl(my_slot, k.centre, 64);
-  double acc[DPL];
+  double acc[CN];
 #pragma unroll
-  for (int e = 0; e < DPL; ++e) acc[e] = 0.0;
+  for (int e = 0; e < CN; ++e) acc[e] = 0.0;
   int members = 0;
-  for (int j = 0; j < k.size; ++j) {
-    const int slot = __shfl(my_slot, j, 64);
+  for (int j0 = 0; j0 < k.size; j0 += G) {
+    const int j = j0 + grp;
+    const int slot = __shfl(my_slot, min(j, k.size - 1), 64);
+    // members of the centre's cluster among the G tokens of this pass (same count in every lane)
+#pragma unroll
+    for (int q = 0; q < G; ++q)
+      if (j0 + q < k.size && __shfl(my_slot, min(j0 + q, k.size - 1), 64) == centre_slot) ++members;
+    if (j >= k.size) continue;
     const T* row = base + (long)bucket_token(g, k, j) * row_stride;
     if (slot == centre_slot) {
+      double x[CN];
+      Chunk<T>::load(row, x);
 #pragma unroll
-      for (int e = 0; e < DPL; ++e) acc[e] += Elem<T>::load(row + e);
-      ++members;
+      for (int e = 0; e < CN; ++e) acc[e] += x[e];
     } else {
-#pragma unroll
-      for (int e = 0; e < DPL; ++e) out[(long)slot * head_dim + e] = row[e];
+      *(uint4*)(out + (long)slot * D) = *(const uint4*)row;
     }
   }
 #pragma unroll
-  for (int e = 0; e < DPL; ++e) Elem<T>::store(out + (long)centre_slot * head_dim + e, acc[e] / (double)members);
+  for (int e = 0; e < CN; ++e) {
+    double v = acc[e];
+#pragma unroll
+    for (int off = CPR; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+    acc[e] = v / (double)members;
+  }
+  if (grp == 0) {
+    T* o = out + (long)centre_slot * D;
+#pragma unroll
+    for (int e = 0; e < CN; ++e) Elem<T>::store(o + e, acc[e]);
+  }
 }
 
 // text rows ride along unchanged behind the L_c pooled rows
@@ -364,17 +422,14 @@ int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const 
   const int rows = (int)(p->Lc + p->d.n_text);
   hipStream_t st = (hipStream_t)stream;
   if (p->d.dtype == VORTA_BF16)
-    hipLaunchKernelGGL((bcs_pool_kernel<uint16_t, 2>), grid, dim3(256), 0, st, (const uint16_t*)src, hl, g,
-                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, p->d.head_dim, assign,
-                       (uint16_t*)dst);
+    hipLaunchKernelGGL((bcs_pool_kernel<uint16_t, 128>), grid, dim3(256), 0, st, (const uint16_t*)src, hl, g,
+                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, assign, (uint16_t*)dst);
   else if (p->d.head_dim == 64)
-    hipLaunchKernelGGL((bcs_pool_kernel<float, 1>), grid, dim3(256), 0, st, (const float*)src, hl, g,
-                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, p->d.head_dim, assign,
-                       (float*)dst);
+    hipLaunchKernelGGL((bcs_pool_kernel<float, 64>), grid, dim3(256), 0, st, (const float*)src, hl, g,
+                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, assign, (float*)dst);
   else
-    hipLaunchKernelGGL((bcs_pool_kernel<float, 2>), grid, dim3(256), 0, st, (const float*)src, hl, g,
-                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, p->d.head_dim, assign,
-                       (float*)dst);
+    hipLaunchKernelGGL((bcs_pool_kernel<float, 128>), grid, dim3(256), 0, st, (const float*)src, hl, g,
+                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, assign, (float*)dst);
   if (int rc = launch_status("bcs_pool_kernel")) return rc;
   if (p->d.n_text > 0) {
     const int cs = chunk_shift(p);
