@@ -193,7 +193,7 @@ def test_row_maxima_that_jump_or_creep_late_in_the_key_stream():
         kh = k[h].float()
         # scores creep up (or down) along the keys; gentler on the core-set heads, whose pooled
         # rows are rounded to bf16 (the 2e-2 bar assumes inputs of about unit variance)
-        kh = kh + (60.0 if cfg.fixed_routes[h] == 0 else 6.0) * ramp * u[None, :]
+        kh = kh + (24.0 if cfg.fixed_routes[h] == 0 else 6.0) * ramp * u[None, :]
         for j, row in ((int(0.45 * N), 100), (int(0.93 * N), 2000), (N - 1, 7)):
             kh[j] = (4.0 if cfg.fixed_routes[h] == 0 else 1.5) * q[h, row].float()   # a late key that dominates one row
         k[h] = kh.to(torch.bfloat16)
