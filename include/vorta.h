@@ -171,7 +171,7 @@ typedef struct vorta_attn_io {
   void* o_c;                    /* [n_lr][L_c + n_text][d]                                     */
 } vorta_attn_io;
 
-/* softmax(scale * Q K^T) V for every head in ONE launch: route 0 over all N keys (Eq. 2),
+/* softmax(scale * Q K^T) V for every head in one call: route 0 over all N keys (Eq. 2),
  * route 1 over the key tiles of vorta_window_runs plus text keys (Algorithm 1), route 2
  * over the pooled core-set rows.  bf16: MFMA contractions, fp32 softmax statistics, P and
  * the output rounded to bf16.  fp32: fp32 throughout. */

@@ -1,7 +1,8 @@
-// bf16 routed attention for gfx950 (CDNA4): flash-style forward, one launch for all heads.
+// bf16 routed attention for gfx950 (CDNA4): flash-style forward.  Two kernels: a software-
+// pipelined one for the dense and core-set segments (further down) and a simpler one for the
+// window segment (first).  Common to both:
 //
-// Workgroup = 4 wavefronts = 128 query rows (32 per wavefront); keys stream through LDS in
-// blocks of 64 rows, double buffered, one barrier per block.  Both contractions run on
+// A wavefront owns 32 query rows; keys stream through LDS in blocks of 64 rows.  Both contractions run on
 // v_mfma_f32_32x32x16_bf16 and are computed TRANSPOSED so that a lane owns one query:
 //     S^T = K Q^T      A = K rows from LDS (one ds_read_b128 per lane), B = Q^T kept in VGPRs
 //     O^T += V^T P^T   A = V^T read from row-major V with ds_read_b64_tr_b16, B = P^T
@@ -12,8 +13,6 @@
 // permutation of the key index; V^T is read with the same permutation.)
 // Softmax statistics are fp32, exp via v_exp_f32 on scores pre-multiplied by log2(e).
 #include <hip/hip_runtime.h>
-
-#include <type_traits>
 
 #include "vorta_attn_common.h"
 
@@ -362,9 +361,10 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 //
 // The iteration is written as 32 slots, one matrix instruction each, separated by scheduling
 // fences: a slot also requests the LDS fragments of the matrix instruction LEAD slots later
-// and carries a few instructions of the softmax (or of the staging).  The accumulators O^T
-// are rescaled to the new row maxima at the END of iteration i (rarely taken branch), after
-// P(i-1) V(i-1) went in and before P(i) V(i) does.  K/V blocks live in a ring of four LDS
+// and carries a few instructions of the softmax (or of the staging).  The softmax keeps a
+// lagging row reference instead of the running maximum (see the reference check in the loop
+// body), so the accumulators O^T are rescaled only on a rarely taken branch at the END of
+// iteration i, after P(i-1) V(i-1) went in and before P(i) V(i) does.  K/V blocks live in a ring of four LDS
 // stages: V(i-1) and K(i+1) are being read, block i waits for its second product, block i+2
 // is being written; one barrier per iteration.  Score tiles and probability fragments
 // alternate between two register sets from one iteration to the next, so nothing is copied.
@@ -372,10 +372,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 namespace {
 constexpr int PIPE_BUFS = 4;
 constexpr int PIPE_LDS_BYTES = PIPE_BUFS * STAGE_ELEMS * 2;
-#ifndef PIPE_LEAD
-#define PIPE_LEAD 2
-#endif
-constexpr int LEAD = PIPE_LEAD;          // slots between a fragment request and its use
+constexpr int LEAD = 2;                  // slots between a fragment request and its use (2..6 measured alike; 2 needs the fewest registers)
 constexpr float P_MAX = 256.f;           // largest probability (relative to the row reference) the fast path accepts
 }  // namespace
 
