@@ -264,9 +264,10 @@ def sampled_rows(cfg, plan, head, rng):
     tt = plan.tile_tokens
     corner = np.nonzero(perm // tt == 0)[0]
     mid = np.nonzero(perm // tt == plan.n_tiles // 2 + plan.tiles[2] // 2)[0]
-    rows = np.concatenate([rng.choice(L, 24, replace=False), corner[:: max(1, len(corner) // 16)],
-                           mid[:: max(1, len(mid) // 16)], np.arange(L - 3, L),
-                           L + np.arange(0, cfg.n_text, 16)])
+    # 512 random rows, every row of a corner tile and of a tile in the middle of the grid, the
+    # last video rows (ragged tail of the last query block) and every text row
+    rows = np.concatenate([rng.choice(L, 512, replace=False), corner, mid, np.arange(L - 3, L),
+                           L + np.arange(cfg.n_text)])
     return np.unique(rows)
 
 
