@@ -127,6 +127,14 @@ int vorta_bcs_slot_bases(const vorta_plan* plan, int32_t* slot_base);
 int vorta_route_partition(const vorta_plan* plan, const uint8_t* routes_host,
                           int32_t* heads_by_route, int32_t counts[3]);
 
+/* Eq. 3: the router of one block, alpha = softmax(T W_R).  t_emb: host float[d_t], the
+ * diffusion timestep embedding; w_r: host float[heads][d_t][3], one d_t x 3 projection per head
+ * (the paper states one per block; per-head gates are what its per-head routing needs -- pass
+ * the same matrix for every head to get per-block gates); alpha_out: host float[heads][3] =
+ * (full, sliding, core-set), each row sums to 1.  Accumulation in double.  Returns
+ * VORTA_EINVAL for null pointers or d_t < 1. */
+int vorta_router_gates(const float* t_emb, const float* w_r, int32_t d_t, int32_t heads, float* alpha_out);
+
 /* Eq. 4: gates alpha[heads][3] = (full, sliding, core-set) -> route codes; a branch is
  * taken only if its gate strictly exceeds both others, every tie goes to full.  Host arrays. */
 int vorta_route_select(const float* alpha_host, int32_t heads, uint8_t* routes_host);

@@ -21,7 +21,7 @@ VORTA_MAX_HEADS = 128
 SYMBOLS = [
     "vorta_strerror", "vorta_last_error", "vorta_plan_create", "vorta_plan_destroy", "vorta_plan_info_get",
     "vorta_tile_permutation", "vorta_window_boxes", "vorta_window_runs", "vorta_bcs_slot_bases",
-    "vorta_route_partition", "vorta_route_select", "vorta_reorder_to_tiles", "vorta_reorder_from_tiles",
+    "vorta_route_partition", "vorta_router_gates", "vorta_route_select", "vorta_reorder_to_tiles", "vorta_reorder_from_tiles",
     "vorta_bcs_build_index", "vorta_bcs_pool", "vorta_attention_routed", "vorta_scatter_back",
     "vorta_workspace_bytes", "vorta_workspace_layout", "vorta_routed_attention_layer",
     "vorta_soft_mixture_workspace_bytes", "vorta_soft_mixture_layer",
@@ -203,6 +203,18 @@ def vorta_route_partition(plan: Plan, routes):
     counts = np.empty(3, dtype=np.int32)
     _check(load_library().vorta_route_partition(plan.handle, _u8p(r), _i32p(heads), _i32p(counts)))
     return heads, counts
+
+
+def vorta_router_gates(t_emb, w_r) -> np.ndarray:
+    t = np.ascontiguousarray(t_emb, dtype=np.float32)
+    w = np.ascontiguousarray(w_r, dtype=np.float32)
+    heads, d_t = w.shape[0], t.shape[0]
+    assert w.shape == (heads, d_t, 3)
+    alpha = np.empty((heads, 3), dtype=np.float32)
+    fp = ctypes.POINTER(ctypes.c_float)
+    _check(load_library().vorta_router_gates(t.ctypes.data_as(fp), w.ctypes.data_as(fp), d_t, heads,
+                                             alpha.ctypes.data_as(fp)))
+    return alpha
 
 
 def vorta_route_select(alpha) -> np.ndarray:

@@ -262,6 +262,23 @@ int vorta_route_partition(const vorta_plan* p, const uint8_t* routes_host, int32
   return VORTA_OK;
 }
 
+int vorta_router_gates(const float* t_emb, const float* w_r, int32_t d_t, int32_t heads, float* alpha_out) {
+  clear_error();
+  if (!t_emb || !w_r || !alpha_out || heads < 0) return fail(VORTA_EINVAL, "null argument");
+  if (d_t < 1) return fail(VORTA_EINVAL, "d_t = %d: the timestep embedding is empty", d_t);
+  for (int h = 0; h < heads; ++h) {
+    const float* w = w_r + (size_t)h * d_t * 3;
+    double z[3] = {0.0, 0.0, 0.0};
+    for (int i = 0; i < d_t; ++i)
+      for (int k = 0; k < 3; ++k) z[k] += (double)t_emb[i] * (double)w[3 * i + k];
+    const double m = std::max(z[0], std::max(z[1], z[2]));
+    double e[3], sum = 0.0;
+    for (int k = 0; k < 3; ++k) { e[k] = std::exp(z[k] - m); sum += e[k]; }
+    for (int k = 0; k < 3; ++k) alpha_out[3 * h + k] = (float)(e[k] / sum);
+  }
+  return VORTA_OK;
+}
+
 int vorta_route_select(const float* alpha, int32_t heads, uint8_t* routes) {
   clear_error();
   if (!alpha || !routes || heads < 0) return fail(VORTA_EINVAL, "null argument");

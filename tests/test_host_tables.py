@@ -128,6 +128,29 @@ def test_route_partition_and_select():
     assert list(vorta.vorta_route_select(alpha[:8])) == [0, 0, 0, 0, 0, 1, 2, 0]
 
 
+def test_router_gates_are_softmax_of_the_projection():
+    """Eq. 3 through the C ABI against the oracle, plus what the mathematics fixes: rows sum to 1,
+    a zero embedding gives uniform gates, adding the same vector to the three columns of W_R
+    changes nothing, and scaling one column up makes its branch win Eq. 4."""
+    rng = np.random.default_rng(3)
+    heads, d_t = 40, 256
+    T = rng.standard_normal(d_t).astype(np.float32)
+    W = (0.1 * rng.standard_normal((heads, d_t, 3))).astype(np.float32)
+    got = vorta.vorta_router_gates(T, W)
+    want = vo.router_gates(T, W)
+    assert got.shape == (heads, 3) and np.abs(got - want).max() < 2e-7
+    assert np.abs(got.sum(1) - 1).max() < 1e-6
+    assert np.allclose(vorta.vorta_router_gates(np.zeros(d_t, np.float32), W), 1 / 3, atol=1e-7)
+    shift = rng.standard_normal((heads, d_t, 1)).astype(np.float32)
+    assert np.abs(vorta.vorta_router_gates(T, W + shift) - got).max() < 1e-5
+    W2 = W.copy()
+    W2[:, :, 2] = 3.0 * T[None, :]            # core-set logit = 3 |T|^2 for every head
+    assert (vorta.vorta_route_select(vorta.vorta_router_gates(T, W2)) == 2).all()
+    with pytest.raises(vorta.VortaError) as e:
+        vorta.vorta_router_gates(np.zeros(0, np.float32), np.zeros((2, 0, 3), np.float32))
+    assert e.value.code == -1
+
+
 def test_bad_descriptions_are_rejected():
     ok = dict(grid=(4, 8, 8), heads=2, head_dim=128, dtype="bf16", tile=(2, 4, 4), window=(3, 3, 3))
     vorta.vorta_plan_create(**ok)
