@@ -192,6 +192,17 @@ int vorta_attention_routed(vorta_plan* plan, const uint8_t* routes_host,
 int vorta_scatter_back(vorta_plan* plan, const uint8_t* routes_host, const void* o_t,
                        const void* o_c, const int32_t* assign, void* out, void* stream);
 
+/* ---- measurement aid ------------------------------------------------------------------------ */
+
+/* Not a step of the method: runs only v_mfma_f32_32x32x16_bf16 (8 wavefronts per workgroup,
+ * `workgroups` workgroups, `iters` x 32 instructions per wavefront) on the operand bits the
+ * caller supplies, so that bench.py can report the matrix rate the chip sustains for a given
+ * data distribution next to the nominal peak.  operands: device, 16 x 64 x 16 bytes (8 A and 8 B
+ * fragments per lane); sink: device float[workgroups * 512]; clocks: device int64[2], receives
+ * shader-clock ticks and 100 MHz ticks of workgroup 0.  FLOPs = workgroups*8*iters*32*32768. */
+int vorta_probe_mfma_rate(const void* operands, int32_t iters, int32_t workgroups, void* sink,
+                          void* clocks, void* stream);
+
 /* ---- the whole path ----------------------------------------------------------------------- */
 
 /* Bytes of device scratch the layer call needs for these routes (internal buffers above). */

@@ -21,7 +21,7 @@ VORTA_MAX_HEADS = 128
 SYMBOLS = [
     "vorta_strerror", "vorta_last_error", "vorta_plan_create", "vorta_plan_destroy", "vorta_plan_info_get",
     "vorta_tile_permutation", "vorta_window_boxes", "vorta_window_runs", "vorta_bcs_slot_bases",
-    "vorta_route_partition", "vorta_router_gates", "vorta_route_select", "vorta_reorder_to_tiles", "vorta_reorder_from_tiles",
+    "vorta_probe_mfma_rate", "vorta_route_partition", "vorta_router_gates", "vorta_route_select", "vorta_reorder_to_tiles", "vorta_reorder_from_tiles",
     "vorta_bcs_build_index", "vorta_bcs_pool", "vorta_attention_routed", "vorta_scatter_back",
     "vorta_workspace_bytes", "vorta_workspace_layout", "vorta_routed_attention_layer",
     "vorta_soft_mixture_workspace_bytes", "vorta_soft_mixture_layer",
@@ -215,6 +215,16 @@ def vorta_router_gates(t_emb, w_r) -> np.ndarray:
     _check(load_library().vorta_router_gates(t.ctypes.data_as(fp), w.ctypes.data_as(fp), d_t, heads,
                                              alpha.ctypes.data_as(fp)))
     return alpha
+
+
+def vorta_probe_mfma_rate(operands: torch.Tensor, iters: int, workgroups: int, stream=None):
+    """Returns (FLOPs issued, sink, clocks); the caller times the call with events."""
+    assert operands.numel() * operands.element_size() >= 16 * 64 * 16
+    sink = torch.empty(workgroups * 512, dtype=torch.float32, device=operands.device)
+    clocks = torch.zeros(2, dtype=torch.int64, device=operands.device)
+    _check(load_library().vorta_probe_mfma_rate(_ptr(operands), iters, workgroups, _ptr(sink), _ptr(clocks),
+                                                _stream(stream)))
+    return workgroups * 8 * iters * 32 * 32768.0, sink, clocks
 
 
 def vorta_route_select(alpha) -> np.ndarray:

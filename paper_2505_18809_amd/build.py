@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvorta.so")
-SOURCES = ["vorta_host.cpp", "vorta_passes.hip", "vorta_attn_f32.hip", "vorta_attn_bf16.hip", "vorta_api.hip"]
+SOURCES = ["vorta_host.cpp", "vorta_passes.hip", "vorta_attn_f32.hip", "vorta_attn_bf16.hip", "vorta_probe.hip", "vorta_api.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
