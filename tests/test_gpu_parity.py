@@ -226,6 +226,34 @@ def test_layer_equals_the_staged_calls_and_is_deterministic():
     assert torch.equal(out, staged)
 
 
+def test_layer_call_replays_from_a_hip_graph():
+    """The layer call is plain kernel launches on the caller's stream (no allocation, no host
+    synchronisation once the plan's tables are on the device), so it can be captured; every
+    replay, with eager work and synchronisations in between, must reproduce the eager output."""
+    cfg = get_config("single")
+    routes = make_routes(cfg).numpy()
+    q, k, v = make_qkv(cfg, DEV)
+    plan = vorta.plan_for(cfg)
+    ws = torch.empty(vorta.vorta_workspace_bytes(plan, routes), dtype=torch.uint8, device=DEV)
+    eager = vorta.vorta_routed_attention_layer(plan, q, k, v, routes, workspace=ws)   # also uploads the tables
+    torch.cuda.synchronize()
+    out = torch.empty_like(q)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            vorta.vorta_routed_attention_layer(plan, q, k, v, routes, out=out, workspace=ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws.random_(0, 255)                      # eager work between replays; every buffer is rewritten by the graph
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep}"
+
+
 def test_soft_mixture_blends_the_three_branches():
     cfg = small_cfg("mix", (4, 4, 6), 3, "bf16", (2, 2, 3), (1, 3, 1), [0, 1, 2])
     q, k, v = make_qkv(cfg, DEV)
