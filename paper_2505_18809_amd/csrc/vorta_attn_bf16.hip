@@ -137,9 +137,11 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   }
 
   // global -> LDS staging: thread moves the 16-byte chunk (tid & 15) of rows (tid >> 4) + STG_ROWS i.
-  // A full block is addressed as (wave-uniform base of the block's first row) + (per-thread
-  // byte offset that never changes), so the loads need no per-block vector address arithmetic;
-  // only the last block of a run clamps its rows to the end of the run.
+  // The key rows of an item are the concatenation of its runs, cut into blocks of BN: a block
+  // that lies inside one run is addressed as (wave-uniform base of its first row) + (per-thread
+  // byte offset that never changes), so its loads need no per-block vector address arithmetic;
+  // a block that crosses into the next run(s) looks every row up in the run list, and the rows
+  // past the end of the last run repeat its last row (they are masked out of the softmax).
   const int ld_row = tid >> 4, ld_col = (tid & 15) * 8;
   const unsigned ld_off0 = 2u * ((unsigned)ld_row * row_stride + (unsigned)ld_col);   // bytes
   const unsigned ld_step = 2u * STG_ROWS * row_stride;
@@ -147,13 +149,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 #define FETCH_FULL(i_, kr_, vr_, kb_, vb_)                          \
   kr_ = *(const uint4*)((kb_) + (ld_off0 + (i_)*ld_step));           \
   vr_ = *(const uint4*)((vb_) + (ld_off0 + (i_)*ld_step));
-#define FETCH_TAIL(i_, kr_, vr_, start_, len_, pos_)                                       \
+#define FETCH_TAIL(i_, kr_, vr_, run_, pos_)                                               \
   {                                                                                        \
-    const unsigned off_ = (unsigned)((start_) + min((pos_) + ld_row + STG_ROWS * (i_), (len_)-1)) * row_stride + ld_col; \
+    const unsigned off_ = (unsigned)packed_row(run_, (pos_) + ld_row + STG_ROWS * (i_)) * row_stride + ld_col; \
     kr_ = *(const uint4*)(K + off_);                                                       \
     vr_ = *(const uint4*)(V + off_);                                                       \
   }
-#define FETCH(start_, len_, pos_)                                                          \
+#define FETCH(run_, start_, len_, pos_)                                                    \
   if ((pos_) + BN <= (len_)) {                                                             \
     const size_t base_ = (size_t)(unsigned)((start_) + (pos_)) * row_stride * 2u;          \
     const char* kb_ = (const char*)K + base_;                                              \
@@ -165,11 +167,11 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       FETCH_FULL(3, kr3, vr3, kb_, vb_)                                                    \
     }                                                                                      \
   } else {                                                                                 \
-    FETCH_TAIL(0, kr0, vr0, start_, len_, pos_)                                            \
-    FETCH_TAIL(1, kr1, vr1, start_, len_, pos_)                                            \
+    FETCH_TAIL(0, kr0, vr0, run_, pos_)                                                    \
+    FETCH_TAIL(1, kr1, vr1, run_, pos_)                                                    \
     if constexpr (STG_PASSES == 4) {                                                       \
-      FETCH_TAIL(2, kr2, vr2, start_, len_, pos_)                                          \
-      FETCH_TAIL(3, kr3, vr3, start_, len_, pos_)                                          \
+      FETCH_TAIL(2, kr2, vr2, run_, pos_)                                                  \
+      FETCH_TAIL(3, kr3, vr3, run_, pos_)                                                  \
     }                                                                                      \
   }
 #define STAGE(buf_)                                                       \
@@ -191,8 +193,19 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   auto run_start = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r]) : 0; };
   auto run_len = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r + 1]) : w.single_len; };
 
-  int n_blocks = 0;
-  for (int r = 0; r < w.n_runs; ++r) n_blocks += (run_len(r) + BN - 1) / BN;
+  int n_keys = 0;
+  for (int r = 0; r < w.n_runs; ++r) n_keys += run_len(r);
+  const int n_blocks = (n_keys + BN - 1) / BN;
+  // row of the key that lies k keys after the start of run r0
+  auto packed_row = [&](int r0, int k) {
+    int rr = r0, len_rr = run_len(r0);
+    while (k >= len_rr && rr + 1 < w.n_runs) {
+      k -= len_rr;
+      ++rr;
+      len_rr = run_len(rr);
+    }
+    return run_start(rr) + min(k, len_rr - 1);
+  };
 
   f32x16 o0, o1, o2, o3;
 #pragma unroll
@@ -200,8 +213,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   float m_run = -INFINITY, l_run = 0.f;
   const float c = a.scale * 1.4426950408889634f;
 
-  int r = 0, pos = 0, start = run_start(0), len = run_len(0);
-  FETCH(start, len, 0)
+  int r = 0, pos = 0, start = run_start(0), len = run_len(0), left = n_keys;   // cursor: run, offset in it, keys left
+  FETCH(r, start, len, 0)
   STAGE(0)
   __syncthreads();
 
@@ -213,15 +226,16 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   for (int it = 0; it < n_blocks; ++it) {
     // cursor of the next block
     int nr = r, npos = pos + BN, nstart = start, nlen = len;
-    if (npos >= len) {
-      nr = r + 1;
-      npos = 0;
-      if (nr < w.n_runs) { nstart = run_start(nr); nlen = run_len(nr); }
+    while (npos >= nlen && nr + 1 < w.n_runs) {
+      npos -= nlen;
+      ++nr;
+      nstart = run_start(nr);
+      nlen = run_len(nr);
     }
     const bool has_next = it + 1 < n_blocks;
-    if (has_next) { FETCH(nstart, nlen, npos) }
+    if (has_next) { FETCH(nr, nstart, nlen, npos) }
 
-    const int n_valid = min(BN, len - pos);
+    const int n_valid = min(BN, left);
     const uint16_t* kp = k_rd + (it & 1) * STAGE_ELEMS;
     const uint16_t* vp = v_rd + (it & 1) * STAGE_ELEMS;
 
@@ -324,6 +338,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 
     __syncthreads();
     r = nr; pos = npos; start = nstart; len = nlen;
+    left -= BN;
   }
 
   DBG_CLK_END(NW == 8)
