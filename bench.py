@@ -166,14 +166,20 @@ def main():
     q_c, k_c, v_c, o_c = (buf(i, n_lr, plan.n_core_tokens) for i in range(4, 8))
     keep_idx = ws[off[8]: off[8] + n_lr * plan.n_core * 4].view(torch.int32).view(n_lr, plan.n_core)
     assign = ws[off[9]: off[9] + n_lr * plan.n_video * 4].view(torch.int32).view(n_lr, plan.n_video)
-    stages = {
-        "reorder_to_tiles": lambda: [vorta.vorta_reorder_to_tiles(plan, s, routes, d) for s, d in ((q, q_t), (k, k_t), (v, v_t))],
+    # what the layer call issues: with bf16 the window kernel gathers rows through the tile
+    # permutation, so there is no reorder pass and no tile-ordered copy
+    gather = cfg.dtype == "bf16"
+    tiled = {} if gather else dict(q_t=q_t, k_t=k_t, v_t=v_t, o_t=o_t)
+    stages = {}
+    if not gather:
+        stages["reorder_to_tiles"] = lambda: [vorta.vorta_reorder_to_tiles(plan, s, routes, d) for s, d in ((q, q_t), (k, k_t), (v, v_t))]
+    stages.update({
         "bcs_build_index": lambda: vorta.vorta_bcs_build_index(plan, k, routes, keep_idx, assign),
         "bcs_pool": lambda: [vorta.vorta_bcs_pool(plan, s, routes, keep_idx, assign, d) for s, d in ((q, q_c), (k, k_c), (v, v_c))],
-        "attention_routed": lambda: vorta.vorta_attention_routed(plan, routes, q=q, k=k, v=v, out=out, q_t=q_t, k_t=k_t, v_t=v_t,
-                                                                  o_t=o_t, q_c=q_c, k_c=k_c, v_c=v_c, o_c=o_c),
-        "scatter_back": lambda: vorta.vorta_scatter_back(plan, routes, o_t, o_c, assign, out),
-    }
+        "attention_routed": lambda: vorta.vorta_attention_routed(plan, routes, q=q, k=k, v=v, out=out, q_c=q_c, k_c=k_c,
+                                                                  v_c=v_c, o_c=o_c, **tiled),
+        "scatter_back": lambda: vorta.vorta_scatter_back(plan, routes, None if gather else o_t, o_c, assign, out),
+    })
     stage_ms = {name: 0.0 for name in stages}
     events = []
     for _ in range(args.steps):
@@ -193,7 +199,7 @@ def main():
         "reorder_to_tiles": 2 * 3 * n_win * N * row,
         "bcs_build_index": n_lr * L * row + n_lr * (Lc + L) * 4,
         "bcs_pool": 3 * n_lr * (N * row + plan.n_core_tokens * row + L * 4),
-        "scatter_back": 2 * (n_win + n_lr) * N * row + n_lr * L * 4,
+        "scatter_back": (0 if gather else 2 * n_win * N * row) + n_lr * (N + plan.n_core_tokens) * row + n_lr * L * 4,
     }
     attn_ms = stage_ms["attention_routed"]
     peak = MFMA_PEAK_TFLOPS[cfg.dtype]
@@ -251,7 +257,7 @@ def main():
                      "flops_per_launch": dom["flops"], "ms_per_launch": dom["ms"],
                      "traffic": ATTN_TRAFFIC_BYTES if args.workload == "wan720p" else None},
         "stages_ms": stage_ms,
-        "memory_passes_GBps": {n: pass_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in pass_bytes if stage_ms[n] > 0},
+        "memory_passes_GBps": {n: pass_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in pass_bytes if stage_ms.get(n, 0) > 0},
     }
     if cfg.dtype == "bf16":
         result["mfma_probe"] = mfma_probe(vorta, torch, dev)

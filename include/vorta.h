@@ -169,7 +169,10 @@ int vorta_bcs_pool(vorta_plan* plan, const void* src, const uint8_t* routes_host
                    const int32_t* keep_idx, const int32_t* assign, void* dst, void* stream);
 
 /* Buffers of the fused attention launch.  Unused groups may be NULL when no head takes
- * that route. */
+ * that route.  bf16 only: q_t, k_t, v_t and o_t may ALL be NULL although heads take route 1 --
+ * the window kernel then gathers the rows of q, k, v through the tile permutation and writes
+ * its output rows straight to their places in `out` (no tile-ordered copies, no reorder
+ * passes); vorta_scatter_back is then called with o_t = NULL.  This is what the layer call does. */
 typedef struct vorta_attn_io {
   const void *q, *k, *v;        /* user layout; read by route-0 heads                          */
   void* out;                    /* user layout; route-0 heads write their rows here            */
@@ -186,7 +189,8 @@ typedef struct vorta_attn_io {
 int vorta_attention_routed(vorta_plan* plan, const uint8_t* routes_host,
                            const vorta_attn_io* io, void* stream);
 
-/* Back to sequence order: route 1 rows by the inverse tile permutation from o_t, route 2
+/* Back to sequence order: route 1 rows by the inverse tile permutation from o_t (skipped when
+ * o_t is NULL: see vorta_attn_io), route 2
  * rows by unpool() -- out[i] = o_c[assign[i]], text rows from o_c[L_c + t] -- into the
  * user-layout out.  Route 0 rows are already in place. */
 int vorta_scatter_back(vorta_plan* plan, const uint8_t* routes_host, const void* o_t,

@@ -32,6 +32,8 @@ int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io,
   a->row_stride0 = ut.row_stride;
   a->qc = io->q_c; a->kc = io->k_c; a->vc = io->v_c; a->oc = io->o_c;
   a->qt = io->q_t; a->kt = io->k_t; a->vt = io->v_t; a->ot = io->o_t;
+  a->tok_of = p->d_tok_of;
+  a->win_gather = io->q_t == nullptr;
   a->runs = p->d_runs;
   a->n_runs = p->d_n_runs;
   a->max_runs = p->max_runs;
@@ -56,16 +58,20 @@ int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io,
   a->end_text = (int)end_text;
   a->scale = p->scale;
   for (int i = 0; i < rl.count[0]; ++i) a->dense_heads[i] = (uint8_t)rl.heads[0][i];
+  for (int i = 0; i < rl.count[1]; ++i) a->win_heads[i] = (uint8_t)rl.heads[1][i];
   return VORTA_OK;
 }
 
 static int attention(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream) {
   if (!io) return fail(VORTA_EINVAL, "io is null");
-  if (rl.count[0]) {
+  const bool gather = rl.count[1] && !io->q_t && !io->k_t && !io->v_t && !io->o_t;   // window heads read q, k, v directly
+  if (gather && p->d.dtype != VORTA_BF16)
+    return fail(VORTA_EINVAL, "the fp32 path needs the tile-ordered copies io.q_t, k_t, v_t, o_t");
+  if (rl.count[0] || gather) {
     VORTA_TRY(check_ptr(io->q, "io.q")); VORTA_TRY(check_ptr(io->k, "io.k"));
     VORTA_TRY(check_ptr(io->v, "io.v")); VORTA_TRY(check_ptr(io->out, "io.out"));
   }
-  if (rl.count[1]) {
+  if (rl.count[1] && !gather) {
     VORTA_TRY(check_ptr(io->q_t, "io.q_t")); VORTA_TRY(check_ptr(io->k_t, "io.k_t"));
     VORTA_TRY(check_ptr(io->v_t, "io.v_t")); VORTA_TRY(check_ptr(io->o_t, "io.o_t"));
   }
@@ -95,10 +101,15 @@ static int layer(vorta_plan* p, const RouteLists& rl, const void* q, const void*
                  const uint8_t* routes, void* out, const Carved& c, void* stream) {
   int32_t* keep_idx = (int32_t*)c.buf[8];
   int32_t* assign = (int32_t*)c.buf[9];
-  // route 1: tokens into 3-D tile order
-  VORTA_TRY(launch_reorder(p, rl, q, c.buf[0], true, stream));
-  VORTA_TRY(launch_reorder(p, rl, k, c.buf[1], true, stream));
-  VORTA_TRY(launch_reorder(p, rl, v, c.buf[2], true, stream));
+  // route 1: with bf16 the window kernel gathers token rows through the tile permutation and
+  // scatters its output rows the same way, so the reorder passes and the tile-ordered copies
+  // are only used by the fp32 path
+  const bool gather = p->d.dtype == VORTA_BF16;
+  if (!gather) {
+    VORTA_TRY(launch_reorder(p, rl, q, c.buf[0], true, stream));
+    VORTA_TRY(launch_reorder(p, rl, k, c.buf[1], true, stream));
+    VORTA_TRY(launch_reorder(p, rl, v, c.buf[2], true, stream));
+  }
   // route 2: core-set index on K, then pool Q, K, V
   VORTA_TRY(launch_bcs_index(p, rl, k, keep_idx, assign, stream));
   VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, c.buf[4], stream));
@@ -106,10 +117,12 @@ static int layer(vorta_plan* p, const RouteLists& rl, const void* q, const void*
   VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, c.buf[6], stream));
   vorta_attn_io io;
   io.q = q; io.k = k; io.v = v; io.out = out;
-  io.q_t = c.buf[0]; io.k_t = c.buf[1]; io.v_t = c.buf[2]; io.o_t = c.buf[3];
+  io.q_t = io.k_t = io.v_t = nullptr;
+  io.o_t = nullptr;
+  if (!gather) { io.q_t = c.buf[0]; io.k_t = c.buf[1]; io.v_t = c.buf[2]; io.o_t = c.buf[3]; }
   io.q_c = c.buf[4]; io.k_c = c.buf[5]; io.v_c = c.buf[6]; io.o_c = c.buf[7];
   VORTA_TRY(attention(p, rl, &io, stream));
-  VORTA_TRY(launch_reorder(p, rl, out, c.buf[3], false, stream));
+  if (!gather) VORTA_TRY(launch_reorder(p, rl, out, c.buf[3], false, stream));
   VORTA_TRY(launch_unpool(p, rl, c.buf[7], assign, out, stream));
   (void)routes;
   return VORTA_OK;
@@ -173,7 +186,7 @@ int vorta_scatter_back(vorta_plan* p, const uint8_t* routes, const void* o_t, co
   RouteLists rl;
   VORTA_TRY(begin(p, routes, &rl));
   if (rl.count[1] || rl.count[2]) VORTA_TRY(check_ptr(out, "out"));
-  if (rl.count[1]) {
+  if (rl.count[1] && o_t) {      // o_t null: the window heads wrote their rows to `out` themselves
     VORTA_TRY(check_ptr(o_t, "o_t"));
     VORTA_TRY(launch_reorder(p, rl, out, const_cast<void*>(o_t), false, stream));
   }

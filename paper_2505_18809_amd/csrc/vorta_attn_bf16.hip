@@ -112,15 +112,19 @@ __device__ unsigned g_dbg_stamps[18];
 #define DBG_CLK_END(cond_)
 #endif
 
-template <int NW>   // wavefronts per workgroup: 4 (two workgroups per CU) or 8 (one)
+// GATHER: the item's rows are tile-order indices into the caller's tensors -- every query,
+// key, value and output row goes through a.tok_of (tile-order index -> token index) instead
+// of living in tile-ordered copies.  The indices of a key block are loaded one block ahead of
+// its rows, so the two dependent loads never wait for each other inside one iteration.
+template <int NW, bool GATHER>   // NW wavefronts per workgroup: 4 (two workgroups per CU) or 8 (one)
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   constexpr int STG_ROWS = 4 * NW, STG_PASSES = BN / STG_ROWS;   // staging: rows per pass, passes per block
   const WorkItem w = decode_item<32 * NW, D>(a, xcd_item(blockIdx.x, gridDim.x, NW == 4));
-  const uint16_t* Q = (const uint16_t*)(w.seg == 0 ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
-  const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
-  const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
-  uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
+  const uint16_t* Q = (const uint16_t*)(w.seg == 0 || GATHER ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
+  const uint16_t* K = (const uint16_t*)(w.seg == 0 || GATHER ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
+  const uint16_t* V = (const uint16_t*)(w.seg == 0 || GATHER ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
+  uint16_t* O = (uint16_t*)(w.seg == 0 || GATHER ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
   const unsigned row_stride = (unsigned)w.row_stride;   // rows * stride < 2^31 elements (checked on the host)
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -130,7 +134,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   // Q^T fragments: lane = query (l32), 8 consecutive dims per 16-wide k slice
   bf16x8 qf[8];
   {
-    const unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    if (GATHER) qrow = (unsigned)a.tok_of[qrow];
     const uint16_t* qp = Q + qrow * row_stride + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * ks));
@@ -189,6 +194,31 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       *(uint4*)(vb_ + 3 * STG_ROWS * VSTR) = vr3;                         \
     }                                                                     \
   }
+  // GATHER: token index of staging row i of a block, and the loads of that row
+  int gi0 = 0, gi1 = 0, gi2 = 0, gi3 = 0;
+#define GATHER_IDX_ROW(i_, gi_, run_, start_, len_, pos_)                                            \
+  gi_ = a.tok_of[(pos_) + BN <= (len_) ? (start_) + (pos_) + ld_row + STG_ROWS * (i_)                 \
+                                       : packed_row(run_, (pos_) + ld_row + STG_ROWS * (i_))];
+#define GATHER_IDX(run_, start_, len_, pos_)               \
+  GATHER_IDX_ROW(0, gi0, run_, start_, len_, pos_)         \
+  GATHER_IDX_ROW(1, gi1, run_, start_, len_, pos_)         \
+  if constexpr (STG_PASSES == 4) {                         \
+    GATHER_IDX_ROW(2, gi2, run_, start_, len_, pos_)       \
+    GATHER_IDX_ROW(3, gi3, run_, start_, len_, pos_)       \
+  }
+#define GATHER_ROW(kr_, vr_, gi_)                                        \
+  {                                                                      \
+    const unsigned off_ = (unsigned)(gi_) * row_stride + ld_col;         \
+    kr_ = *(const uint4*)(K + off_);                                     \
+    vr_ = *(const uint4*)(V + off_);                                     \
+  }
+#define GATHER_ROWS()                 \
+  GATHER_ROW(kr0, vr0, gi0)           \
+  GATHER_ROW(kr1, vr1, gi1)           \
+  if constexpr (STG_PASSES == 4) {    \
+    GATHER_ROW(kr2, vr2, gi2)         \
+    GATHER_ROW(kr3, vr3, gi3)         \
+  }
   // run bounds are the same for every lane: keep them in scalar registers
   auto run_start = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r]) : 0; };
   auto run_len = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r + 1]) : w.single_len; };
@@ -213,8 +243,30 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   float m_run = -INFINITY, l_run = 0.f;
   const float c = a.scale * 1.4426950408889634f;
 
-  int r = 0, pos = 0, start = run_start(0), len = run_len(0), left = n_keys;   // cursor: run, offset in it, keys left
-  FETCH(r, start, len, 0)
+  // fetch cursor (run, offset in it, its first row and length): the next block to request --
+  // its rows, or with GATHER its token indices (the rows follow one iteration later)
+  int fr = 0, fpos = 0, fstart = run_start(0), flen = run_len(0), left = n_keys;
+  auto advance = [&]() {
+    fpos += BN;
+    while (fpos >= flen && fr + 1 < w.n_runs) {
+      fpos -= flen;
+      ++fr;
+      fstart = run_start(fr);
+      flen = run_len(fr);
+    }
+  };
+  if constexpr (GATHER) {
+    GATHER_IDX(fr, fstart, flen, fpos)
+    advance();
+    GATHER_ROWS()
+    if (n_blocks > 1) {
+      GATHER_IDX(fr, fstart, flen, fpos)
+      advance();
+    }
+  } else {
+    FETCH(fr, fstart, flen, fpos)
+    advance();
+  }
   STAGE(0)
   __syncthreads();
 
@@ -224,16 +276,17 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   const uint16_t* v_rd = smem + KTILE + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3);
 
   for (int it = 0; it < n_blocks; ++it) {
-    // cursor of the next block
-    int nr = r, npos = pos + BN, nstart = start, nlen = len;
-    while (npos >= nlen && nr + 1 < w.n_runs) {
-      npos -= nlen;
-      ++nr;
-      nstart = run_start(nr);
-      nlen = run_len(nr);
-    }
     const bool has_next = it + 1 < n_blocks;
-    if (has_next) { FETCH(nr, nstart, nlen, npos) }
+    if constexpr (GATHER) {
+      if (has_next) { GATHER_ROWS() }                     // block it+1, indices loaded an iteration ago
+      if (it + 2 < n_blocks) {
+        GATHER_IDX(fr, fstart, flen, fpos)                // block it+2
+        advance();
+      }
+    } else if (has_next) {
+      FETCH(fr, fstart, flen, fpos)
+      advance();
+    }
 
     const int n_valid = min(BN, left);
     const uint16_t* kp = k_rd + (it & 1) * STAGE_ELEMS;
@@ -337,7 +390,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
     }
 
     __syncthreads();
-    r = nr; pos = npos; start = nstart; len = nlen;
     left -= BN;
   }
 
@@ -358,11 +410,17 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int row = (lane >> 4) + 4 * i;
-    if (32 * wave + row < w.n_rows)
-      *(uint4*)(O + (unsigned)(w.row0 + 32 * wave + row) * row_stride + (lane & 15) * 8) =
-          *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+    if (32 * wave + row < w.n_rows) {
+      unsigned orow = w.row0 + 32 * wave + row;
+      if (GATHER) orow = (unsigned)a.tok_of[orow];
+      *(uint4*)(O + orow * row_stride + (lane & 15) * 8) = *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+    }
   }
 }
+#undef GATHER_IDX_ROW
+#undef GATHER_IDX
+#undef GATHER_ROW
+#undef GATHER_ROWS
 
 
 // ------------------------------------------------------------------------------------------
@@ -723,7 +781,8 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   static std::once_flag once;
   static int attr_rc = VORTA_OK;
   std::call_once(once, [] {
-    attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4>, "attn_bf16_kernel<4>", LDS_BYTES);
+    attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4, false>, "attn_bf16_kernel<4, false>", LDS_BYTES);
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4, true>, "attn_bf16_kernel<4, true>", LDS_BYTES);
     if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel, "attn_bf16_pipe_kernel", PIPE_LDS_BYTES);
   });
   if (attr_rc) return attr_rc;
@@ -737,7 +796,12 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   if (a.end_text > 0)
     hipLaunchKernelGGL(attn_bf16_pipe_kernel, dim3(a.end_text), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
   if (int rc = fill_attn_args(p, win_rl, io, BM, &a)) return rc;
-  if (a.end_text > 0) hipLaunchKernelGGL(attn_bf16_kernel<4>, dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+  if (a.end_text > 0) {
+    if (a.win_gather)
+      hipLaunchKernelGGL((attn_bf16_kernel<4, true>), dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+    else
+      hipLaunchKernelGGL((attn_bf16_kernel<4, false>), dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(VORTA_EHIP, "launch of attn_bf16 kernels: %s", hipGetErrorString(e));
   return VORTA_OK;

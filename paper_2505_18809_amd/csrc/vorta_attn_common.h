@@ -26,6 +26,10 @@ struct AttnArgs {
   // route 1: [n_win][N][d] in tile order
   const void *qt, *kt, *vt;
   void* ot;
+  // route 1 without tile-ordered copies (qt == null): rows of the caller's tensors are gathered
+  // through tok_of (tile-order index -> token index); win_heads = head id of each window slot
+  const int* tok_of;                // [N]
+  int win_gather;
   const int* runs;                  // [n_tiles][max_runs][2]
   const int* n_runs;                // [n_tiles]
   int max_runs;
@@ -35,6 +39,7 @@ struct AttnArgs {
   int end_dense, end_core, end_tile, end_text;   // cumulative item counts
   float scale;
   uint8_t dense_heads[VORTA_MAX_HEADS];
+  uint8_t win_heads[VORTA_MAX_HEADS];
 };
 
 struct WorkItem {
@@ -75,8 +80,8 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
     const int slot = item / per_head, r = item - slot * per_head;
     const int tile = r / a.qb_tile, qb = r - tile * a.qb_tile;
     w.seg = 2;
-    w.q_off = w.kv_off = w.o_off = (long)slot * a.N * D;
-    w.row_stride = D;
+    w.q_off = w.kv_off = w.o_off = a.win_gather ? a.win_heads[slot] * a.head_stride0 : (long)slot * a.N * D;
+    w.row_stride = a.win_gather ? a.row_stride0 : D;
     w.row0 = tile * a.tile_tokens + qb * BM;
     w.n_rows = min(BM, a.tile_tokens - qb * BM);
     w.runs = a.runs + (long)tile * a.max_runs * 2;
@@ -86,8 +91,8 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
     item -= a.end_tile;
     const int slot = item / a.qb_text, qb = item - slot * a.qb_text;
     w.seg = 2;
-    w.q_off = w.kv_off = w.o_off = (long)slot * a.N * D;
-    w.row_stride = D;
+    w.q_off = w.kv_off = w.o_off = a.win_gather ? a.win_heads[slot] * a.head_stride0 : (long)slot * a.N * D;
+    w.row_stride = a.win_gather ? a.row_stride0 : D;
     w.row0 = a.L + qb * BM;
     w.n_rows = min(BM, a.n_text - qb * BM);
     w.single_len = a.N;

@@ -24,13 +24,15 @@ struct vorta_plan {
   std::vector<int32_t> n_runs;   // [n_tiles]
   std::vector<int32_t> slot_base;  // [n_buckets + 1]
 
-  // device copies of runs / n_runs / slot_base, uploaded on first device use
+  // device copies of runs / n_runs / slot_base and the tile-order -> sequence-order token table
+  // (identity for the text rows), uploaded on first device use
   std::mutex mu;
   bool on_device = false;
   int device = -1;
   int32_t* d_runs = nullptr;
   int32_t* d_n_runs = nullptr;
   int32_t* d_slot_base = nullptr;
+  int32_t* d_tok_of = nullptr;   // [N]
 };
 
 namespace vorta {

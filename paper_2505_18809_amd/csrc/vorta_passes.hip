@@ -35,6 +35,14 @@ int ensure_device_tables(vorta_plan* p) {
   VORTA_HIP(hipMemcpy(p->d_n_runs, p->n_runs.data(), p->n_runs.size() * sizeof(int32_t), hipMemcpyHostToDevice));
   VORTA_HIP(hipMemcpy(p->d_slot_base, p->slot_base.data(), p->slot_base.size() * sizeof(int32_t),
                       hipMemcpyHostToDevice));
+  {
+    std::vector<int32_t> perm((size_t)p->L), tok_of((size_t)p->N);
+    if (int rc = vorta_tile_permutation(p, perm.data())) return rc;
+    for (int64_t i = 0; i < p->L; ++i) tok_of[perm[i]] = (int32_t)i;
+    for (int64_t i = p->L; i < p->N; ++i) tok_of[i] = (int32_t)i;
+    VORTA_HIP(hipMalloc(&p->d_tok_of, tok_of.size() * sizeof(int32_t)));
+    VORTA_HIP(hipMemcpy(p->d_tok_of, tok_of.data(), tok_of.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+  }
   p->device = dev;
   p->on_device = true;
   return VORTA_OK;
@@ -492,6 +500,7 @@ extern "C" int vorta_plan_destroy(vorta_plan* p) {
     (void)hipFree(p->d_runs);
     (void)hipFree(p->d_n_runs);
     (void)hipFree(p->d_slot_base);
+    (void)hipFree(p->d_tok_of);
   }
   delete p;
   return VORTA_OK;

@@ -224,6 +224,13 @@ def test_layer_equals_the_staged_calls_and_is_deterministic():
     vorta.vorta_scatter_back(plan, routes, o_t, o_c, assign, staged)
     torch.cuda.synchronize()
     assert torch.equal(out, staged)
+    # the same without tile-ordered copies: the window kernel gathers rows through the tile
+    # permutation and writes its rows to their places itself
+    direct = torch.zeros_like(q)
+    vorta.vorta_attention_routed(plan, routes, q=q, k=k, v=v, out=direct, q_c=q_c, k_c=k_c, v_c=v_c, o_c=o_c)
+    vorta.vorta_scatter_back(plan, routes, None, o_c, assign, direct)
+    torch.cuda.synchronize()
+    assert torch.equal(out, direct)
 
 
 def test_layer_call_replays_from_a_hip_graph():
