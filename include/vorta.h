@@ -209,7 +209,8 @@ int vorta_probe_mfma_rate(const void* operands, int32_t iters, int32_t workgroup
 
 /* ---- the whole path ----------------------------------------------------------------------- */
 
-/* Bytes of device scratch the layer call needs for these routes (internal buffers above). */
+/* Bytes of device scratch the layer call needs for these routes (internal buffers above; with
+ * bf16 the four tile-ordered buffers are empty because the layer call does not make them). */
 int vorta_workspace_bytes(const vorta_plan* plan, const uint8_t* routes_host, size_t* bytes);
 
 /* Byte offsets of the internal buffers inside the workspace, in the order

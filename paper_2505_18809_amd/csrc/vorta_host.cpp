@@ -295,7 +295,8 @@ int vorta_route_select(const float* alpha, int32_t heads, uint8_t* routes) {
 // Workspace: q_t,k_t,v_t,o_t,q_c,k_c,v_c,o_c,keep_idx,assign, each 256-byte aligned.
 static void workspace_sizes(const vorta_plan* p, const RouteLists& rl, size_t sizes[10]) {
   const size_t row = (size_t)p->d.head_dim * p->elem_bytes;
-  const size_t tiled = (size_t)rl.count[1] * p->N * row;
+  // tile-ordered copies: only the fp32 layer call makes them (bf16 gathers rows in the window kernel)
+  const size_t tiled = p->d.dtype == VORTA_BF16 ? 0 : (size_t)rl.count[1] * p->N * row;
   const size_t core = (size_t)rl.count[2] * (p->Lc + p->d.n_text) * row;
   for (int i = 0; i < 4; ++i) sizes[i] = tiled;
   for (int i = 4; i < 8; ++i) sizes[i] = core;

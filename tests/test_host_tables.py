@@ -171,7 +171,11 @@ def test_workspace_layout_is_aligned_and_ordered():
     total = vorta.vorta_workspace_bytes(plan, routes)
     assert off[0] == 0 and all(o % 256 == 0 for o in off) and off == sorted(off)
     row = 128 * 2
-    assert off[1] - off[0] == 12 * plan.n_tokens * row
+    assert off[1] - off[0] == 0 and off[4] == 0      # bf16: no tile-ordered copies in the layer call
     assert off[5] - off[4] == 10 * plan.n_core_tokens * row
     assert off[9] - off[8] >= 10 * plan.n_core * 4
     assert total >= off[9] + 10 * plan.n_video * 4
+    cfg32 = get_config("tiny")                        # fp32: four tile-ordered buffers per window head
+    plan32 = vorta.plan_for(cfg32)
+    off32 = vorta.vorta_workspace_layout(plan32, np.array([1, 1], dtype=np.uint8))
+    assert off32[1] - off32[0] == 2 * plan32.n_tokens * 64 * 4
