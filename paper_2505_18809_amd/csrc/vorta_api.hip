@@ -56,6 +56,7 @@ int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io,
   a->end_core = (int)end_core;
   a->end_tile = (int)end_tile;
   a->end_text = (int)end_text;
+  a->split_from = 0x7fffffff;
   a->scale = p->scale;
   for (int i = 0; i < rl.count[0]; ++i) a->dense_heads[i] = (uint8_t)rl.heads[0][i];
   for (int i = 0; i < rl.count[1]; ++i) a->win_heads[i] = (uint8_t)rl.heads[1][i];

@@ -14,6 +14,8 @@
 // Softmax statistics are fp32, exp via v_exp_f32 on scores pre-multiplied by log2(e).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "vorta_attn_common.h"
 
 namespace vorta {
@@ -98,14 +100,16 @@ __device__ __forceinline__ lds_ptr opaque(lds_ptr p) {
 #define MFMA(a_, b_, c_) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b_, c_, 0, 0, 0)
 
 #ifdef VORTA_DEBUG_CLOCKS
-__device__ long long g_dbg_clk[4];
+__device__ long long g_dbg_clk[16];
 __device__ unsigned g_dbg_stamps[18];
 #define DBG_CLK_BEGIN const long long dbg_c0 = __builtin_amdgcn_s_memtime(), dbg_r0 = __builtin_amdgcn_s_memrealtime();
 #define DBG_CLK_END(cond_)                                              \
-  if ((cond_) && blockIdx.x == 300 && threadIdx.x == 0) {                \
-    g_dbg_clk[0] = __builtin_amdgcn_s_memtime() - dbg_c0;                \
-    g_dbg_clk[1] = __builtin_amdgcn_s_memrealtime() - dbg_r0;            \
-    g_dbg_clk[2] = n_blocks;                                             \
+  if ((cond_) && threadIdx.x == 0 && (blockIdx.x == 300 || blockIdx.x == 1500 || blockIdx.x == 3000 || blockIdx.x == 4100)) { \
+    const int s_ = blockIdx.x == 300 ? 0 : blockIdx.x == 1500 ? 4 : blockIdx.x == 3000 ? 8 : 12;   \
+    g_dbg_clk[s_] = __builtin_amdgcn_s_memtime() - dbg_c0;               \
+    g_dbg_clk[s_ + 1] = __builtin_amdgcn_s_memrealtime() - dbg_r0;       \
+    g_dbg_clk[s_ + 2] = n_blocks;                                        \
+    g_dbg_clk[s_ + 3] = dbg_r0;                                          \
   }
 #else
 #define DBG_CLK_BEGIN
@@ -464,6 +468,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
   uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
   const unsigned row_stride = (unsigned)w.row_stride;
 
+  if (w.n_rows <= 0) return;       // second half of a split item whose rows all lie in the first half
+
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
   DBG_CLK_BEGIN
@@ -735,9 +741,19 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
   // is odd the last iteration works on a block of masked keys (probabilities 0) and only its
   // second product, of the real last block, matters.  The scores an iteration computes for
   // the block after the last one come from a ring stage holding a copy of the last block.
-  for (int i = 0; i < n_blocks; i += 2) {
-    body(i, sa0, sa1, sb0, sb1, pa, pb);
-    body(i + 1, sb0, sb1, sa0, sa1, pb, pa);
+  if (32 * wave < w.n_rows) {
+    for (int i = 0; i < n_blocks; i += 2) {
+      body(i, sa0, sa1, sb0, sb1, pa, pb);
+      body(i + 1, sb0, sb1, sa0, sa1, pb, pa);
+    }
+  } else {
+    // helper wavefront (no query rows: upper half of a split item, or past the last row): it only
+    // keeps its share of the staging going, with the same barriers as the others
+    for (int i = 0; i < ((n_blocks + 1) & ~1); ++i) {
+      stage_all((i + 2) & 3);     // block i+2 leaves the registers
+      fetch_all();                // block i+3 enters
+      __syncthreads();
+    }
   }
 #undef SLOT_FENCE
 
@@ -793,8 +809,12 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   win_rl.count[0] = win_rl.count[2] = 0;
   AttnArgs a;
   if (int rc = fill_attn_args(p, long_rl, io, BM_LONG, &a)) return rc;
-  if (a.end_text > 0)
-    hipLaunchKernelGGL(attn_bf16_pipe_kernel, dim3(a.end_text), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
+  if (a.end_text > 0) {
+    // the last items (at most one per two CUs) go out as half-row items: see AttnArgs::split_from
+    const int n_split = std::min(a.end_text, p->n_cus / 2);
+    a.split_from = a.end_text - n_split;
+    hipLaunchKernelGGL(attn_bf16_pipe_kernel, dim3(a.end_text + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
+  }
   if (int rc = fill_attn_args(p, win_rl, io, BM, &a)) return rc;
   if (a.end_text > 0) {
     if (a.win_gather)
@@ -814,6 +834,6 @@ extern "C" int vorta_debug_stamps(unsigned* out18) {
   return hipMemcpyFromSymbol(out18, HIP_SYMBOL(vorta::g_dbg_stamps), sizeof(unsigned) * 18) == hipSuccess ? 0 : -6;
 }
 extern "C" int vorta_debug_clocks(long long* out4) {
-  return hipMemcpyFromSymbol(out4, HIP_SYMBOL(vorta::g_dbg_clk), sizeof(long long) * 4) == hipSuccess ? 0 : -6;
+  return hipMemcpyFromSymbol(out4, HIP_SYMBOL(vorta::g_dbg_clk), sizeof(long long) * 16) == hipSuccess ? 0 : -6;
 }
 #endif

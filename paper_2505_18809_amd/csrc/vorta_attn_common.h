@@ -35,6 +35,12 @@ struct AttnArgs {
   int max_runs;
   int N, Nc, L, n_text;
   int n_tiles, tile_tokens;
+  // The last work items of a launch leave most CUs idle while a few finish them.  Items with
+  // index >= split_from are therefore issued as two items of BM / 2 rows each (grid index
+  // split_from + 2 j + h -> rows [h BM / 2, (h + 1) BM / 2) of item split_from + j); a workgroup
+  // whose upper wavefronts have no rows runs them as helpers (staging only), which takes about
+  // half the time of a full item.  split_from = INT_MAX: no split.
+  int split_from;
   int qb_dense, qb_core, qb_tile, qb_text;   // q-blocks per head / core-set / tile / text part
   int end_dense, end_core, end_tile, end_text;   // cumulative item counts
   float scale;
@@ -57,6 +63,11 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
   WorkItem w;
   w.runs = nullptr;
   w.n_runs = 1;
+  int half = -1;
+  if (item >= a.split_from) {
+    half = (item - a.split_from) & 1;
+    item = a.split_from + ((item - a.split_from) >> 1);
+  }
   if (item < a.end_dense) {
     const int slot = item / a.qb_dense, qb = item - slot * a.qb_dense;
     w.seg = 0;
@@ -96,6 +107,10 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
     w.row0 = a.L + qb * BM;
     w.n_rows = min(BM, a.n_text - qb * BM);
     w.single_len = a.N;
+  }
+  if (half >= 0) {          // n_rows may come out <= 0: the workgroup then has nothing to do
+    w.row0 += half * (BM / 2);
+    w.n_rows = min(BM / 2, w.n_rows - half * (BM / 2));
   }
   return w;
 }

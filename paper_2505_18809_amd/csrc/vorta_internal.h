@@ -29,6 +29,7 @@ struct vorta_plan {
   std::mutex mu;
   bool on_device = false;
   int device = -1;
+  int n_cus = 256;               // compute units of that device
   int32_t* d_runs = nullptr;
   int32_t* d_n_runs = nullptr;
   int32_t* d_slot_base = nullptr;

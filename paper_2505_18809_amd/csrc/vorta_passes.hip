@@ -43,6 +43,11 @@ int ensure_device_tables(vorta_plan* p) {
     VORTA_HIP(hipMalloc(&p->d_tok_of, tok_of.size() * sizeof(int32_t)));
     VORTA_HIP(hipMemcpy(p->d_tok_of, tok_of.data(), tok_of.size() * sizeof(int32_t), hipMemcpyHostToDevice));
   }
+  {
+    int cus = 0;
+    VORTA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (cus > 0) p->n_cus = cus;
+  }
   p->device = dev;
   p->on_device = true;
   return VORTA_OK;
