@@ -257,6 +257,12 @@ def main():
                      "flops_per_launch": dom["flops"], "ms_per_launch": dom["ms"],
                      "traffic": ATTN_TRAFFIC_BYTES if args.workload == "wan720p" else None},
         "stages_ms": stage_ms,
+        # the attention call is two launches; the window launch is what the dominant kernel leaves of it
+        "attention_launches": {
+            "dense+core-set": {"ms": dom["ms"], "TFLOP/s": dom["flops"] / (dom["ms"] * 1e-3) / 1e12},
+            "window": ({"ms": attn_ms - dom["ms"], "TFLOP/s": per_route[1] / ((attn_ms - dom["ms"]) * 1e-3) / 1e12}
+                       if counts[1] and attn_ms > dom["ms"] else None),
+        },
         "memory_passes_GBps": {n: pass_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in pass_bytes if stage_ms.get(n, 0) > 0},
     }
     if cfg.dtype == "bf16":

@@ -230,15 +230,17 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   int n_keys = 0;
   for (int r = 0; r < w.n_runs; ++r) n_keys += run_len(r);
   const int n_blocks = (n_keys + BN - 1) / BN;
-  // row of the key that lies k keys after the start of run r0
+  // row of the key that lies k keys after the start of run r0 (k differs between lanes, so the
+  // run it lands in does too: per-lane loads of the run table, not the scalar copies)
   auto packed_row = [&](int r0, int k) {
-    int rr = r0, len_rr = run_len(r0);
+    if (!w.runs) return min(k, w.single_len - 1);
+    int rr = r0, len_rr = w.runs[2 * r0 + 1];
     while (k >= len_rr && rr + 1 < w.n_runs) {
       k -= len_rr;
       ++rr;
-      len_rr = run_len(rr);
+      len_rr = w.runs[2 * rr + 1];
     }
-    return run_start(rr) + min(k, len_rr - 1);
+    return w.runs[2 * rr] + min(k, len_rr - 1);
   };
 
   f32x16 o0, o1, o2, o3;

@@ -158,6 +158,25 @@ def test_ragged_shapes_text_tokens_and_mixed_routes(dtype, d):
     check_layer(cfg, cfg.fixed_routes, layout=0)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_small_layers(seed):
+    """Shapes drawn from a seed: grids that make ragged last blocks, one- and many-run windows,
+    run lists crossing 64-key blocks, tiles above and below a query block, text tokens or none,
+    both layouts, every route mix -- each head against the oracle on all rows."""
+    rng = np.random.default_rng(1000 + seed)
+    tile = tuple(int(rng.integers(1, 5)) for _ in range(3))
+    reps = tuple(int(rng.integers(1, 5)) for _ in range(3))
+    grid = tuple(t * r for t, r in zip(tile, reps))
+    window = tuple(int(rng.choice([1, 3, 5])) for _ in range(3))
+    heads = int(rng.integers(1, 6))
+    routes = [int(r) for r in rng.integers(0, 3, heads)]
+    n_text = int(rng.choice([0, 0, 5, 70]))
+    cfg = small_cfg(f"rand{seed}", grid, heads, "bf16", tile, window, routes, n_text=n_text, seed=50 + seed,
+                    bucket=tuple(int(b) for b in rng.choice([1, 2, 3], 3)))
+    say(f"seed {seed}: grid {grid} tile {tile} window {window} text {n_text} routes {routes} bucket {cfg.bucket}")
+    check_layer(cfg, routes, layout=int(rng.integers(0, 2)), center_mode=int(rng.integers(0, 2)))
+
+
 def test_window_identity_centres_and_wide_windows():
     cfg = small_cfg("ident", (4, 8, 8), 2, "bf16", (2, 2, 2), (1, 3, 5), [1, 1])
     check_layer(cfg, cfg.fixed_routes, center_mode=1)
