@@ -171,7 +171,8 @@ def test_seeded_random_small_layers(seed):
     heads = int(rng.integers(1, 6))
     routes = [int(r) for r in rng.integers(0, 3, heads)]
     n_text = int(rng.choice([0, 0, 5, 70]))
-    cfg = small_cfg(f"rand{seed}", grid, heads, "bf16", tile, window, routes, n_text=n_text, seed=50 + seed,
+    dtype, d = (("fp32", 64) if seed % 4 == 3 else ("bf16", 128))     # fp32: the exact path and the reorder passes
+    cfg = small_cfg(f"rand{seed}", grid, heads, dtype, tile, window, routes, d=d, n_text=n_text, seed=50 + seed,
                     bucket=tuple(int(b) for b in rng.choice([1, 2, 3], 3)))
     say(f"seed {seed}: grid {grid} tile {tile} window {window} text {n_text} routes {routes} bucket {cfg.bucket}")
     check_layer(cfg, routes, layout=int(rng.integers(0, 2)), center_mode=int(rng.integers(0, 2)))
