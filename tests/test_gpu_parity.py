@@ -321,12 +321,15 @@ def sampled_rows(cfg, plan, head, rng):
     mid = np.nonzero(perm // tt == plan.n_tiles // 2 + plan.tiles[2] // 2)[0]
     # 512 random rows, every row of a corner tile and of a tile in the middle of the grid, the
     # last video rows (ragged tail of the last query block) and every text row
-    rows = np.concatenate([rng.choice(L, 512, replace=False), corner, mid, np.arange(L - 3, L),
+    # (tiles of more than 128 tokens: every other / third ... row, so that they cost no more)
+    step = max(1, len(corner) // 128)
+    n_random = 512 if plan.tile_tokens <= 128 else 192
+    rows = np.concatenate([rng.choice(L, n_random, replace=False), corner[::step], mid[::step], np.arange(L - 3, L),
                            L + np.arange(cfg.n_text)])
     return np.unique(rows)
 
 
-@pytest.mark.parametrize("name", ["wan480p", "wan720p", "hunyuan720p"])
+@pytest.mark.parametrize("name", ["wan480p", "wan720p", "hunyuan720p", "paper720p"])
 def test_full_size_layer_on_sampled_rows(name):
     cfg = get_config(name)
     routes = make_routes(cfg).numpy()
