@@ -460,14 +460,19 @@ typedef __attribute__((address_space(3))) u32x4* lds_u4_wptr;
 
 __device__ __forceinline__ float elem_of(const f32x16& t0, const f32x16& t1, int e) { return e < 16 ? t0[e] : t1[e - 16]; }
 
+// WIN: window items read through the tile permutation (see the GATHER flag of the window kernel
+// above): rows of the item are tile-order indices, translated by a.tok_of; the key rows are the
+// concatenation of the tile's runs cut into 64-key blocks.  Used when a tile has more than 128
+// tokens, i.e. fills more than half of a 256-row workgroup.
+template <bool WIN>
 __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   constexpr int STG_ROWS = 32;
-  const WorkItem w = decode_item<BM_LONG, D>(a, blockIdx.x);
-  const uint16_t* Q = (const uint16_t*)(w.seg == 0 ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
-  const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
-  const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
-  uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
+  const WorkItem w = decode_item<BM_LONG, D>(a, xcd_item(blockIdx.x, gridDim.x, WIN));
+  const uint16_t* Q = (const uint16_t*)(w.seg == 0 || WIN ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
+  const uint16_t* K = (const uint16_t*)(w.seg == 0 || WIN ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
+  const uint16_t* V = (const uint16_t*)(w.seg == 0 || WIN ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
+  uint16_t* O = (uint16_t*)(w.seg == 0 || WIN ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
   const unsigned row_stride = (unsigned)w.row_stride;
 
   if (w.n_rows <= 0) return;       // second half of a split item whose rows all lie in the first half
@@ -478,7 +483,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
 
   bf16x8 qf[8];
   {
-    const unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    if (WIN) qrow = (unsigned)a.tok_of[qrow];
     const uint16_t* qp = Q + qrow * row_stride + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * ks));
@@ -486,8 +492,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
 
   auto run_start = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r]) : 0; };
   auto run_len = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r + 1]) : w.single_len; };
-  int n_blocks = 0;
-  for (int r = 0; r < w.n_runs; ++r) n_blocks += (run_len(r) + BN - 1) / BN;
+  int n_keys = 0;
+  for (int r = 0; r < w.n_runs; ++r) n_keys += run_len(r);
+  const int n_blocks = (n_keys + BN - 1) / BN;   // dense / core-set: one run
 
   // ---- global -> register -> LDS staging: thread moves the 16-byte chunk (tid & 15) of rows
   // (tid >> 4) and (tid >> 4) + 32 of K and of V.  The fetch stream walks the run list one
@@ -521,15 +528,71 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     v_wr[(buf * STAGE_ELEMS) / 8] = vr0;
     v_wr[(buf * STAGE_ELEMS + STG_ROWS * VSTR) / 8] = vr1;
   };
-  auto fetch_all = [&]() {
-    fetch_cursor();
-    const unsigned o0_ = row_off(0), o1_ = row_off(1);
+  // WIN: token indices of this thread's two staging rows of the NEXT block whose rows will be
+  // loaded (gi0, gi1), looked up one block ahead of the rows; win_at / win_idx produce them for
+  // the block under the fetch cursor (uniform parameters first, then the per-lane lookup).
+  int gi0 = 0, gi1 = 0;
+  int wi_run = 0, wi_first = 0, wi_pos = 0;
+  bool wi_inside = true;
+  auto packed_row = [&](int r0, int k) {      // row of the key k keys after the start of run r0 (per-lane run walk)
+    if (!w.runs) return min(k, w.single_len - 1);
+    int rr = r0, len_rr = w.runs[2 * r0 + 1];
+    while (k >= len_rr && rr + 1 < w.n_runs) {
+      k -= len_rr;
+      ++rr;
+      len_rr = w.runs[2 * rr + 1];
+    }
+    return w.runs[2 * rr] + min(k, len_rr - 1);
+  };
+  auto win_at = [&]() {            // note the block under the cursor, advance the cursor (scalar work only)
+    wi_run = fr;
+    wi_pos = fpos;
+    wi_first = fstart + fpos;
+    wi_inside = fpos + BN <= flen;
+    fpos += BN;
+    while (fpos >= flen && fr + 1 < w.n_runs) {
+      fpos -= flen;
+      ++fr;
+      fstart = run_start(fr);
+      flen = run_len(fr);
+    }
+  };
+  auto win_idx = [&]() {           // token indices of the noted block
+    int t0, t1;
+    if (wi_inside) {
+      t0 = wi_first + ld_row;
+      t1 = t0 + STG_ROWS;
+    } else {
+      t0 = packed_row(wi_run, wi_pos + ld_row);
+      t1 = packed_row(wi_run, wi_pos + ld_row + STG_ROWS);
+    }
+    gi0 = a.tok_of[t0];
+    gi1 = a.tok_of[t1];
+  };
+  auto win_off = [&](int gi) { return __umul24((unsigned)gi, row_stride) + (unsigned)ld_col; };
+  auto fetch_all = [&]() {         // rows of the next block into the staging registers
+    unsigned o0_, o1_;
+    if constexpr (WIN) {
+      o0_ = win_off(gi0);
+      o1_ = win_off(gi1);
+      win_at();
+      win_idx();                   // indices of the block after it
+    } else {
+      fetch_cursor();
+      o0_ = row_off(0);
+      o1_ = row_off(1);
+    }
     kr0 = ld16(K, o0_); vr0 = ld16(V, o0_);
     kr1 = ld16(K, o1_); vr1 = ld16(V, o1_);
   };
   // valid keys of the blocks in compute order
   int cr = 0, cpos = 0, clen = flen, cblk = 0;
   auto next_valid = [&]() {      // 0 past the last block: a block of masked keys adds nothing
+    if constexpr (WIN) {
+      const int nv = min(BN, max(0, n_keys - BN * cblk));
+      ++cblk;
+      return nv;
+    }
     const int nv = cblk < n_blocks ? min(BN, clen - cpos) : 0;
     ++cblk;
     if (cpos + BN < clen) {
@@ -542,6 +605,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     return nv;
   };
 
+  if constexpr (WIN) {             // prime the index pipeline with block 0
+    win_at();
+    win_idx();
+  }
   fetch_all();
   stage_all(0);
   fetch_all();
@@ -604,7 +671,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     const lds_ptr vq = opaque(v_rd + ((i ? i - 1 : 0) & 3) * STAGE_ELEMS);
     const lds_ptr kq = opaque(k_rd + ((i + 1) & 3) * STAGE_ELEMS);
     const int wbuf = (i + 2) & 3;
-    fetch_cursor();                                  // block i+3 (scalar work and branches: before the slots)
+    if constexpr (WIN) win_at();                     // block i+4: its token indices are looked up in slot 27
+    else fetch_cursor();                             // block i+3 (scalar work and branches: before the slots)
     bf16x8 vf[16], kf[16];
     auto v_req = [&](int n) { vf[n] = v_frag(vq, n); };
     auto k_req = [&](int n) { kf[n] = lds_frag3(kq + 32 * (n & 1) * LSTR + 16 * (n >> 1)); };
@@ -671,9 +739,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
         else ps0 = pair_sum(u[0][p & 7], ps0);
       }
       if (n == 22) {                                 // block i+3: addresses, then one load per slot
-        off0 = row_off(0);
-        off1 = row_off(1);
+        off0 = WIN ? win_off(gi0) : row_off(0);
+        off1 = WIN ? win_off(gi1) : row_off(1);
       }
+      if (WIN && n == 27) win_idx();                 // block i+4
       // ---- staging: block i+2 leaves the registers (slots 12-15), block i+3 enters (23-26)
       if (n == 12) k_wr[(wbuf * STAGE_ELEMS) / 8] = kr0;
       if (n == 13) k_wr[(wbuf * STAGE_ELEMS + STG_ROWS * LSTR) / 8] = kr1;
@@ -783,9 +852,11 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int row = (lane >> 4) + 4 * i;
-    if (32 * wave + row < w.n_rows)
-      *(uint4*)(O + (unsigned)(w.row0 + 32 * wave + row) * row_stride + (lane & 15) * 8) =
-          *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+    if (32 * wave + row < w.n_rows) {
+      unsigned orow = w.row0 + 32 * wave + row;
+      if (WIN) orow = (unsigned)a.tok_of[orow];
+      *(uint4*)(O + orow * row_stride + (lane & 15) * 8) = *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+    }
   }
 }
 
@@ -801,7 +872,8 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   std::call_once(once, [] {
     attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4, false>, "attn_bf16_kernel<4, false>", LDS_BYTES);
     if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4, true>, "attn_bf16_kernel<4, true>", LDS_BYTES);
-    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel, "attn_bf16_pipe_kernel", PIPE_LDS_BYTES);
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<false>, "attn_bf16_pipe_kernel<false>", PIPE_LDS_BYTES);
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true>, "attn_bf16_pipe_kernel<true>", PIPE_LDS_BYTES);
   });
   if (attr_rc) return attr_rc;
   // dense + core-set heads: pipelined kernel, 256-row workgroups; window heads: one 128-row
@@ -815,10 +887,17 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
     // the last items (at most one per two CUs) go out as half-row items: see AttnArgs::split_from
     const int n_split = std::min(a.end_text, p->n_cus / 2);
     a.split_from = a.end_text - n_split;
-    hipLaunchKernelGGL(attn_bf16_pipe_kernel, dim3(a.end_text + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(attn_bf16_pipe_kernel<false>, dim3(a.end_text + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
   }
-  if (int rc = fill_attn_args(p, win_rl, io, BM, &a)) return rc;
-  if (a.end_text > 0) {
+  // window heads: tiles of more than 128 tokens fill a 256-row workgroup well enough for the
+  // pipelined kernel (it needs the gather form); smaller tiles get one 128-row workgroup each
+  const bool win_pipe = io->q_t == nullptr && p->tile_tokens > BM;
+  if (int rc = fill_attn_args(p, win_rl, io, win_pipe ? BM_LONG : BM, &a)) return rc;
+  if (a.end_text > 0 && win_pipe) {
+    const int n_split = std::min(a.end_text, p->n_cus / 2);
+    a.split_from = a.end_text - n_split;
+    hipLaunchKernelGGL(attn_bf16_pipe_kernel<true>, dim3(a.end_text + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
+  } else if (a.end_text > 0) {
     if (a.win_gather)
       hipLaunchKernelGGL((attn_bf16_kernel<4, true>), dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
     else

@@ -164,14 +164,17 @@ def test_seeded_random_small_layers(seed):
     run lists crossing 64-key blocks, tiles above and below a query block, text tokens or none,
     both layouts, every route mix -- each head against the oracle on all rows."""
     rng = np.random.default_rng(1000 + seed)
-    tile = tuple(int(rng.integers(1, 5)) for _ in range(3))
-    reps = tuple(int(rng.integers(1, 5)) for _ in range(3))
+    big = seed % 3 == 2                     # tiles of more than 128 tokens take the pipelined window path
+    tile = tuple(int(rng.integers(4, 8)) for _ in range(3)) if big else tuple(int(rng.integers(1, 5)) for _ in range(3))
+    reps = tuple(int(rng.integers(1, 4 if big else 5)) for _ in range(3))
     grid = tuple(t * r for t, r in zip(tile, reps))
     window = tuple(int(rng.choice([1, 3, 5])) for _ in range(3))
     heads = int(rng.integers(1, 6))
     routes = [int(r) for r in rng.integers(0, 3, heads)]
     n_text = int(rng.choice([0, 0, 5, 70]))
-    dtype, d = (("fp32", 64) if seed % 4 == 3 else ("bf16", 128))     # fp32: the exact path and the reorder passes
+    # fp32: the exact path and the reorder passes -- on the small grids only (its 1e-5 bar is the
+    # Tiny config's; fp32 accumulation over thousands of keys is at 1.3e-5)
+    dtype, d = (("fp32", 64) if seed % 4 == 3 and not big else ("bf16", 128))
     cfg = small_cfg(f"rand{seed}", grid, heads, dtype, tile, window, routes, d=d, n_text=n_text, seed=50 + seed,
                     bucket=tuple(int(b) for b in rng.choice([1, 2, 3], 3)))
     say(f"seed {seed}: grid {grid} tile {tile} window {window} text {n_text} routes {routes} bucket {cfg.bucket}")
