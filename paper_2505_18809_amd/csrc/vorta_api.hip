@@ -24,7 +24,7 @@ static int begin(vorta_plan* p, const uint8_t* routes, RouteLists* rl) {
   return ensure_device_tables(p);
 }
 
-int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, AttnArgs* a) {
+int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, int win_part, AttnArgs* a) {
   std::memset(a, 0, sizeof(*a));
   const UserTensor ut = user_tensor(p, io->q);
   a->q0 = io->q; a->k0 = io->k; a->v0 = io->v; a->o0 = io->out;
@@ -47,15 +47,15 @@ int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io,
   a->qb_core = (a->Nc + BM - 1) / BM;
   a->qb_tile = (a->tile_tokens + BM - 1) / BM;
   a->qb_text = (a->n_text + BM - 1) / BM;
-  const long end_dense = (long)rl.count[0] * a->qb_dense;
+  const long end_text = win_part & WIN_TEXT ? (long)rl.count[1] * a->qb_text : 0;
+  const long end_dense = end_text + (long)rl.count[0] * a->qb_dense;
   const long end_core = end_dense + (long)rl.count[2] * a->qb_core;
-  const long end_tile = end_core + (long)rl.count[1] * a->n_tiles * a->qb_tile;
-  const long end_text = end_tile + (long)rl.count[1] * a->qb_text;
-  if (end_text > 0x7fffffffL) return fail(VORTA_ESHAPE, "%ld work items exceed the grid limit", end_text);
+  const long end_tile = end_core + (win_part & WIN_TILES ? (long)rl.count[1] * a->n_tiles * a->qb_tile : 0);
+  if (end_tile > 0x7fffffffL) return fail(VORTA_ESHAPE, "%ld work items exceed the grid limit", end_tile);
+  a->end_text = (int)end_text;
   a->end_dense = (int)end_dense;
   a->end_core = (int)end_core;
   a->end_tile = (int)end_tile;
-  a->end_text = (int)end_text;
   a->split_from = 0x7fffffff;
   a->scale = p->scale;
   for (int i = 0; i < rl.count[0]; ++i) a->dense_heads[i] = (uint8_t)rl.heads[0][i];

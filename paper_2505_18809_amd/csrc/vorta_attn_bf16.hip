@@ -876,32 +876,31 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
     if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true>, "attn_bf16_pipe_kernel<true>", PIPE_LDS_BYTES);
   });
   if (attr_rc) return attr_rc;
-  // dense + core-set heads: pipelined kernel, 256-row workgroups; window heads: one 128-row
-  // workgroup per tile
-  RouteLists long_rl = rl, win_rl = rl;
-  long_rl.count[1] = 0;
+  // Long items -- dense heads, core-set heads and the text rows of the window heads, which
+  // attend to every row -- run on the pipelined kernel in 256-row workgroups.
+  RouteLists win_rl = rl;
   win_rl.count[0] = win_rl.count[2] = 0;
   AttnArgs a;
-  if (int rc = fill_attn_args(p, long_rl, io, BM_LONG, &a)) return rc;
-  if (a.end_text > 0) {
+  if (int rc = fill_attn_args(p, rl, io, BM_LONG, WIN_TEXT, &a)) return rc;
+  if (a.end_tile > 0) {
     // the last items (at most one per two CUs) go out as half-row items: see AttnArgs::split_from
-    const int n_split = std::min(a.end_text, p->n_cus / 2);
-    a.split_from = a.end_text - n_split;
-    hipLaunchKernelGGL(attn_bf16_pipe_kernel<false>, dim3(a.end_text + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
+    const int n_split = std::min(a.end_tile, p->n_cus / 2);
+    a.split_from = a.end_tile - n_split;
+    hipLaunchKernelGGL(attn_bf16_pipe_kernel<false>, dim3(a.end_tile + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
   }
-  // window heads: tiles of more than 128 tokens fill a 256-row workgroup well enough for the
+  // Window tiles: tiles of more than 128 tokens fill a 256-row workgroup well enough for the
   // pipelined kernel (it needs the gather form); smaller tiles get one 128-row workgroup each
   const bool win_pipe = io->q_t == nullptr && p->tile_tokens > BM;
-  if (int rc = fill_attn_args(p, win_rl, io, win_pipe ? BM_LONG : BM, &a)) return rc;
-  if (a.end_text > 0 && win_pipe) {
-    const int n_split = std::min(a.end_text, p->n_cus / 2);
-    a.split_from = a.end_text - n_split;
-    hipLaunchKernelGGL(attn_bf16_pipe_kernel<true>, dim3(a.end_text + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
-  } else if (a.end_text > 0) {
+  if (int rc = fill_attn_args(p, win_rl, io, win_pipe ? BM_LONG : BM, WIN_TILES, &a)) return rc;
+  if (a.end_tile > 0 && win_pipe) {
+    const int n_split = std::min(a.end_tile, p->n_cus / 2);
+    a.split_from = a.end_tile - n_split;
+    hipLaunchKernelGGL(attn_bf16_pipe_kernel<true>, dim3(a.end_tile + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
+  } else if (a.end_tile > 0) {
     if (a.win_gather)
-      hipLaunchKernelGGL((attn_bf16_kernel<4, true>), dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+      hipLaunchKernelGGL((attn_bf16_kernel<4, true>), dim3(a.end_tile), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
     else
-      hipLaunchKernelGGL((attn_bf16_kernel<4, false>), dim3(a.end_text), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+      hipLaunchKernelGGL((attn_bf16_kernel<4, false>), dim3(a.end_tile), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(VORTA_EHIP, "launch of attn_bf16 kernels: %s", hipGetErrorString(e));

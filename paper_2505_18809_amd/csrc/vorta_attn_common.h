@@ -1,12 +1,14 @@
 // Work decomposition shared by the attention kernels.
 //
-// One launch covers every head of the layer.  Its grid is four consecutive segments of
-// work items, longest items first so the short ones fill the tail of the launch:
+// A launch covers some or all heads of the layer.  Its grid is up to four consecutive segments
+// of work items, longest items first so the short ones fill the tail of the launch:
+//   [ route 1: (slot, q-block over the text rows)         | keys: rows [0, N)                  ]
 //   [ route 0: (head, q-block) over all N rows            | keys: rows [0, N) of the head      ]
 //   [ route 2: (slot, q-block) over L_c + n_text rows     | keys: all rows of the core-set     ]
 //   [ route 1: (slot, tile, q-block inside the tile)      | keys: the tile's run list          ]
-//   [ route 1: (slot, q-block over the text rows)         | keys: rows [0, N)                  ]
-// A work item is BM query rows; its keys are a short list of runs of consecutive rows.
+// A work item is BM query rows; its keys are a short list of runs of consecutive rows.  The
+// text rows of a window head attend to every row, so their items cost as much as those of a
+// full-attention head and sit with them at the front.
 #pragma once
 
 #include <cstdint>
@@ -42,7 +44,7 @@ struct AttnArgs {
   // half the time of a full item.  split_from = INT_MAX: no split.
   int split_from;
   int qb_dense, qb_core, qb_tile, qb_text;   // q-blocks per head / core-set / tile / text part
-  int end_dense, end_core, end_tile, end_text;   // cumulative item counts
+  int end_text, end_dense, end_core, end_tile;   // cumulative item counts, in grid order; end_tile = all
   float scale;
   uint8_t dense_heads[VORTA_MAX_HEADS];
   uint8_t win_heads[VORTA_MAX_HEADS];
@@ -68,7 +70,16 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
     half = (item - a.split_from) & 1;
     item = a.split_from + ((item - a.split_from) >> 1);
   }
-  if (item < a.end_dense) {
+  if (item < a.end_text) {
+    const int slot = item / a.qb_text, qb = item - slot * a.qb_text;
+    w.seg = a.win_gather ? 0 : 2;   // gathered: rows of the caller's tensors, like a dense head
+    w.q_off = w.kv_off = w.o_off = a.win_gather ? a.win_heads[slot] * a.head_stride0 : (long)slot * a.N * D;
+    w.row_stride = a.win_gather ? a.row_stride0 : D;
+    w.row0 = a.L + qb * BM;
+    w.n_rows = min(BM, a.n_text - qb * BM);
+    w.single_len = a.N;
+  } else if (item < a.end_dense) {
+    item -= a.end_text;
     const int slot = item / a.qb_dense, qb = item - slot * a.qb_dense;
     w.seg = 0;
     w.q_off = w.kv_off = w.o_off = a.dense_heads[slot] * a.head_stride0;
@@ -85,7 +96,7 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
     w.row0 = qb * BM;
     w.n_rows = min(BM, a.Nc - w.row0);
     w.single_len = a.Nc;
-  } else if (item < a.end_tile) {
+  } else {
     item -= a.end_core;
     const int per_head = a.n_tiles * a.qb_tile;
     const int slot = item / per_head, r = item - slot * per_head;
@@ -98,15 +109,6 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
     w.runs = a.runs + (long)tile * a.max_runs * 2;
     w.n_runs = a.n_runs[tile];
     w.single_len = 0;
-  } else {
-    item -= a.end_tile;
-    const int slot = item / a.qb_text, qb = item - slot * a.qb_text;
-    w.seg = 2;
-    w.q_off = w.kv_off = w.o_off = a.win_gather ? a.win_heads[slot] * a.head_stride0 : (long)slot * a.N * D;
-    w.row_stride = a.win_gather ? a.row_stride0 : D;
-    w.row0 = a.L + qb * BM;
-    w.n_rows = min(BM, a.n_text - qb * BM);
-    w.single_len = a.N;
   }
   if (half >= 0) {          // n_rows may come out <= 0: the workgroup then has nothing to do
     w.row0 += half * (BM / 2);
@@ -127,7 +129,11 @@ __device__ __forceinline__ int xcd_item(int block, int n, bool chunked) {
   return xcd * q + min(xcd, r) + loc;
 }
 
-// Fills everything of AttnArgs that does not depend on the kernel's block size.
-int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, AttnArgs* a);
+// Work of the window heads (route 1) that a launch includes.
+enum WindowPart { WIN_NONE = 0, WIN_TEXT = 1, WIN_TILES = 2, WIN_ALL = 3 };
+
+// Fills AttnArgs for a launch over the heads of rl with BM-row work items; win_part selects
+// which items of the window heads it carries.
+int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, int win_part, AttnArgs* a);
 
 }  // namespace vorta

@@ -85,12 +85,12 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const AttnArgs a) {
 
 int launch_attention_f32(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream) {
   AttnArgs a;
-  if (int rc = fill_attn_args(p, rl, io, 64, &a)) return rc;
-  if (a.end_text == 0) return VORTA_OK;
+  if (int rc = fill_attn_args(p, rl, io, 64, WIN_ALL, &a)) return rc;
+  if (a.end_tile == 0) return VORTA_OK;
   if (p->d.head_dim == 64)
-    hipLaunchKernelGGL(attn_f32_kernel<64>, dim3(a.end_text), dim3(64), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(attn_f32_kernel<64>, dim3(a.end_tile), dim3(64), 0, (hipStream_t)stream, a);
   else
-    hipLaunchKernelGGL(attn_f32_kernel<128>, dim3(a.end_text), dim3(64), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(attn_f32_kernel<128>, dim3(a.end_tile), dim3(64), 0, (hipStream_t)stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(VORTA_EHIP, "launch of attn_f32_kernel: %s", hipGetErrorString(e));
   return VORTA_OK;
