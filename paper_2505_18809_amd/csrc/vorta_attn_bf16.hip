@@ -99,6 +99,47 @@ __device__ __forceinline__ lds_ptr opaque(lds_ptr p) {
 
 #define MFMA(a_, b_, c_) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b_, c_, 0, 0, 0)
 
+// Run list of a work item.  It is the same for every lane and no kernel writes it, so it is
+// read as constant memory: with a wave-uniform index that is a scalar load, whose result lands
+// in a scalar register and whose wait does not include the vector loads in flight.
+typedef const __attribute__((address_space(4))) int* const_int_ptr;
+struct RunList {
+  const_int_ptr runs;      // (start, length) pairs; null: the single run {0, single_len}
+  int n_runs, single_len;
+  __device__ __forceinline__ explicit RunList(const WorkItem& w)
+      : runs((const_int_ptr)(uintptr_t)w.runs), n_runs(w.n_runs), single_len(w.single_len) {}
+  __device__ __forceinline__ int start(int r) const { return runs ? runs[2 * r] : 0; }
+  __device__ __forceinline__ int len(int r) const { return runs ? runs[2 * r + 1] : single_len; }
+};
+
+// Rows of keys j0 + step i (i < NR) of the 64-key block that begins pos keys into run r, whose
+// first row is s and whose length is len (r, pos, s, len wave-uniform; j0 per lane).  A block
+// that reaches past the end of run r continues in the following runs: they are walked with
+// uniform control flow, each lane keeping the row of the run its key falls in.  Keys past the
+// end of the last run repeat its last row (they are masked out of the softmax).
+template <int NR>
+__device__ __forceinline__ void block_rows(const RunList& rl, int r, int pos, int s, int len, int j0, int step,
+                                           int (&rows)[NR]) {
+  int k[NR];
+#pragma unroll
+  for (int i = 0; i < NR; ++i) {
+    k[i] = pos + j0 + step * i;
+    rows[i] = s + min(k[i], len - 1);
+  }
+  int end = pos + BN;
+  while (end > len && r + 1 < rl.n_runs) {
+    end -= len;
+#pragma unroll
+    for (int i = 0; i < NR; ++i) k[i] -= len;
+    ++r;
+    s = rl.start(r);
+    len = rl.len(r);
+#pragma unroll
+    for (int i = 0; i < NR; ++i)
+      if (k[i] >= 0) rows[i] = s + min(k[i], len - 1);
+  }
+}
+
 #ifdef VORTA_DEBUG_CLOCKS
 __device__ long long g_dbg_clk[16];
 __device__ unsigned g_dbg_stamps[18];
@@ -158,9 +199,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 #define FETCH_FULL(i_, kr_, vr_, kb_, vb_)                          \
   kr_ = *(const uint4*)((kb_) + (ld_off0 + (i_)*ld_step));           \
   vr_ = *(const uint4*)((vb_) + (ld_off0 + (i_)*ld_step));
-#define FETCH_TAIL(i_, kr_, vr_, run_, pos_)                                               \
+#define FETCH_TAIL(kr_, vr_, row_)                                                         \
   {                                                                                        \
-    const unsigned off_ = (unsigned)packed_row(run_, (pos_) + ld_row + STG_ROWS * (i_)) * row_stride + ld_col; \
+    const unsigned off_ = (unsigned)(row_) * row_stride + ld_col;                          \
     kr_ = *(const uint4*)(K + off_);                                                       \
     vr_ = *(const uint4*)(V + off_);                                                       \
   }
@@ -176,11 +217,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       FETCH_FULL(3, kr3, vr3, kb_, vb_)                                                    \
     }                                                                                      \
   } else {                                                                                 \
-    FETCH_TAIL(0, kr0, vr0, run_, pos_)                                                    \
-    FETCH_TAIL(1, kr1, vr1, run_, pos_)                                                    \
+    int rows_[STG_PASSES];                                                                 \
+    block_rows<STG_PASSES>(rl, run_, pos_, start_, len_, ld_row, STG_ROWS, rows_);         \
+    FETCH_TAIL(kr0, vr0, rows_[0])                                                         \
+    FETCH_TAIL(kr1, vr1, rows_[1])                                                         \
     if constexpr (STG_PASSES == 4) {                                                       \
-      FETCH_TAIL(2, kr2, vr2, run_, pos_)                                                  \
-      FETCH_TAIL(3, kr3, vr3, run_, pos_)                                                  \
+      FETCH_TAIL(kr2, vr2, rows_[2])                                                       \
+      FETCH_TAIL(kr3, vr3, rows_[3])                                                       \
     }                                                                                      \
   }
 #define STAGE(buf_)                                                       \
@@ -200,15 +243,16 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   }
   // GATHER: token index of staging row i of a block, and the loads of that row
   int gi0 = 0, gi1 = 0, gi2 = 0, gi3 = 0;
-#define GATHER_IDX_ROW(i_, gi_, run_, start_, len_, pos_)                                            \
-  gi_ = a.tok_of[(pos_) + BN <= (len_) ? (start_) + (pos_) + ld_row + STG_ROWS * (i_)                 \
-                                       : packed_row(run_, (pos_) + ld_row + STG_ROWS * (i_))];
-#define GATHER_IDX(run_, start_, len_, pos_)               \
-  GATHER_IDX_ROW(0, gi0, run_, start_, len_, pos_)         \
-  GATHER_IDX_ROW(1, gi1, run_, start_, len_, pos_)         \
-  if constexpr (STG_PASSES == 4) {                         \
-    GATHER_IDX_ROW(2, gi2, run_, start_, len_, pos_)       \
-    GATHER_IDX_ROW(3, gi3, run_, start_, len_, pos_)       \
+#define GATHER_IDX(run_, start_, len_, pos_)                                               \
+  {                                                                                        \
+    int rows_[STG_PASSES];                                                                 \
+    block_rows<STG_PASSES>(rl, run_, pos_, start_, len_, ld_row, STG_ROWS, rows_);         \
+    gi0 = a.tok_of[rows_[0]];                                                              \
+    gi1 = a.tok_of[rows_[1]];                                                              \
+    if constexpr (STG_PASSES == 4) {                                                       \
+      gi2 = a.tok_of[rows_[2]];                                                            \
+      gi3 = a.tok_of[rows_[3]];                                                            \
+    }                                                                                      \
   }
 #define GATHER_ROW(kr_, vr_, gi_)                                        \
   {                                                                      \
@@ -223,25 +267,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
     GATHER_ROW(kr2, vr2, gi2)         \
     GATHER_ROW(kr3, vr3, gi3)         \
   }
-  // run bounds are the same for every lane: keep them in scalar registers
-  auto run_start = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r]) : 0; };
-  auto run_len = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r + 1]) : w.single_len; };
+  const RunList rl(w);
+  auto run_start = [&](int r) { return rl.start(r); };
+  auto run_len = [&](int r) { return rl.len(r); };
 
   int n_keys = 0;
   for (int r = 0; r < w.n_runs; ++r) n_keys += run_len(r);
   const int n_blocks = (n_keys + BN - 1) / BN;
-  // row of the key that lies k keys after the start of run r0 (k differs between lanes, so the
-  // run it lands in does too: per-lane loads of the run table, not the scalar copies)
-  auto packed_row = [&](int r0, int k) {
-    if (!w.runs) return min(k, w.single_len - 1);
-    int rr = r0, len_rr = w.runs[2 * r0 + 1];
-    while (k >= len_rr && rr + 1 < w.n_runs) {
-      k -= len_rr;
-      ++rr;
-      len_rr = w.runs[2 * rr + 1];
-    }
-    return w.runs[2 * rr] + min(k, len_rr - 1);
-  };
 
   f32x16 o0, o1, o2, o3;
 #pragma unroll
@@ -411,19 +443,23 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
     u.y = pack_bf16(acc_[4 * q4 + 2] * inv, acc_[4 * q4 + 3] * inv);                 \
     *(uint2*)(st + l32 * LSTR + 32 * (dt_) + 8 * q4 + 4 * g) = u;                    \
   }
+  // output rows of this lane (row (lane >> 4) + 4 i of the wavefront's 32): looked up together,
+  // ahead of the barrier, so the stores below do not wait for one lookup each
+  unsigned orow[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    orow[i] = w.row0 + min(32 * wave + (lane >> 4) + 4 * i, w.n_rows - 1);
+    if (GATHER) orow[i] = (unsigned)a.tok_of[orow[i]];
+  }
   STORE_TILE(0, o0) STORE_TILE(1, o1) STORE_TILE(2, o2) STORE_TILE(3, o3)
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int row = (lane >> 4) + 4 * i;
-    if (32 * wave + row < w.n_rows) {
-      unsigned orow = w.row0 + 32 * wave + row;
-      if (GATHER) orow = (unsigned)a.tok_of[orow];
-      *(uint4*)(O + orow * row_stride + (lane & 15) * 8) = *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
-    }
+    if (32 * wave + row < w.n_rows)
+      *(uint4*)(O + orow[i] * row_stride + (lane & 15) * 8) = *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
   }
 }
-#undef GATHER_IDX_ROW
 #undef GATHER_IDX
 #undef GATHER_ROW
 #undef GATHER_ROWS
@@ -490,8 +526,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * ks));
   }
 
-  auto run_start = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r]) : 0; };
-  auto run_len = [&](int r) { return w.runs ? __builtin_amdgcn_readfirstlane(w.runs[2 * r + 1]) : w.single_len; };
+  const RunList rl(w);
+  auto run_start = [&](int r) { return rl.start(r); };
+  auto run_len = [&](int r) { return rl.len(r); };
   int n_keys = 0;
   for (int r = 0; r < w.n_runs; ++r) n_keys += run_len(r);
   const int n_blocks = (n_keys + BN - 1) / BN;   // dense / core-set: one run
@@ -532,23 +569,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
   // loaded (gi0, gi1), looked up one block ahead of the rows; win_at / win_idx produce them for
   // the block under the fetch cursor (uniform parameters first, then the per-lane lookup).
   int gi0 = 0, gi1 = 0;
-  int wi_run = 0, wi_first = 0, wi_pos = 0;
-  bool wi_inside = true;
-  auto packed_row = [&](int r0, int k) {      // row of the key k keys after the start of run r0 (per-lane run walk)
-    if (!w.runs) return min(k, w.single_len - 1);
-    int rr = r0, len_rr = w.runs[2 * r0 + 1];
-    while (k >= len_rr && rr + 1 < w.n_runs) {
-      k -= len_rr;
-      ++rr;
-      len_rr = w.runs[2 * rr + 1];
-    }
-    return w.runs[2 * rr] + min(k, len_rr - 1);
-  };
+  int wi_run = 0, wi_pos = 0, wi_start = 0, wi_len = 1;
   auto win_at = [&]() {            // note the block under the cursor, advance the cursor (scalar work only)
     wi_run = fr;
     wi_pos = fpos;
-    wi_first = fstart + fpos;
-    wi_inside = fpos + BN <= flen;
+    wi_start = fstart;
+    wi_len = flen;
     fpos += BN;
     while (fpos >= flen && fr + 1 < w.n_runs) {
       fpos -= flen;
@@ -558,16 +584,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     }
   };
   auto win_idx = [&]() {           // token indices of the noted block
-    int t0, t1;
-    if (wi_inside) {
-      t0 = wi_first + ld_row;
-      t1 = t0 + STG_ROWS;
-    } else {
-      t0 = packed_row(wi_run, wi_pos + ld_row);
-      t1 = packed_row(wi_run, wi_pos + ld_row + STG_ROWS);
-    }
-    gi0 = a.tok_of[t0];
-    gi1 = a.tok_of[t1];
+    int rows[2];
+    block_rows<2>(rl, wi_run, wi_pos, wi_start, wi_len, ld_row, STG_ROWS, rows);
+    gi0 = a.tok_of[rows[0]];
+    gi1 = a.tok_of[rows[1]];
   };
   auto win_off = [&](int gi) { return __umul24((unsigned)gi, row_stride) + (unsigned)ld_col; };
   auto fetch_all = [&]() {         // rows of the next block into the staging registers
@@ -847,16 +867,19 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.f / l_tot;
   uint16_t* st = smem + wave * 32 * LSTR;
+  unsigned orow[8];                // looked up together, ahead of the barrier
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    orow[i] = w.row0 + min(32 * wave + (lane >> 4) + 4 * i, w.n_rows - 1);
+    if (WIN) orow[i] = (unsigned)a.tok_of[orow[i]];
+  }
   STORE_TILE(0, o[0]) STORE_TILE(1, o[1]) STORE_TILE(2, o[2]) STORE_TILE(3, o[3])
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int row = (lane >> 4) + 4 * i;
-    if (32 * wave + row < w.n_rows) {
-      unsigned orow = w.row0 + 32 * wave + row;
-      if (WIN) orow = (unsigned)a.tok_of[orow];
-      *(uint4*)(O + orow * row_stride + (lane & 15) * 8) = *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
-    }
+    if (32 * wave + row < w.n_rows)
+      *(uint4*)(O + orow[i] * row_stride + (lane & 15) * 8) = *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
   }
 }
 
