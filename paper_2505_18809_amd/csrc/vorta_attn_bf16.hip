@@ -41,6 +41,7 @@ constexpr int VSTR = 144;       // V block
 constexpr int KTILE = BN * LSTR;
 constexpr int STAGE_ELEMS = BN * (LSTR + VSTR);   // one K block + one V block
 constexpr int LDS_BYTES = 2 * STAGE_ELEMS * 2;
+constexpr float P_MAX = 256.f;  // largest probability (relative to the row reference) the softmax fast path accepts
 }  // namespace
 
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
@@ -293,6 +294,9 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       flen = run_len(fr);
     }
   };
+  // Prologue: block 0 goes to LDS, the rows of block 1 wait in the staging registers (and with
+  // GATHER the indices of block 2 in gi*).  Iteration it then writes block it + 1 to the other
+  // buffer first thing and requests block it + 2, so a row has a whole iteration to arrive.
   if constexpr (GATHER) {
     GATHER_IDX(fr, fstart, flen, fpos)
     advance();
@@ -301,11 +305,21 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       GATHER_IDX(fr, fstart, flen, fpos)
       advance();
     }
+    STAGE(0)
+    if (n_blocks > 1) { GATHER_ROWS() }
+    if (n_blocks > 2) {
+      GATHER_IDX(fr, fstart, flen, fpos)
+      advance();
+    }
   } else {
     FETCH(fr, fstart, flen, fpos)
     advance();
+    STAGE(0)
+    if (n_blocks > 1) {
+      FETCH(fr, fstart, flen, fpos)
+      advance();
+    }
   }
-  STAGE(0)
   __syncthreads();
 
   // per-lane LDS read offsets
@@ -314,14 +328,14 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   const uint16_t* v_rd = smem + KTILE + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3);
 
   for (int it = 0; it < n_blocks; ++it) {
-    const bool has_next = it + 1 < n_blocks;
+    if (it + 1 < n_blocks) { STAGE((it + 1) & 1) }        // rows requested an iteration ago
     if constexpr (GATHER) {
-      if (has_next) { GATHER_ROWS() }                     // block it+1, indices loaded an iteration ago
-      if (it + 2 < n_blocks) {
-        GATHER_IDX(fr, fstart, flen, fpos)                // block it+2
+      if (it + 2 < n_blocks) { GATHER_ROWS() }            // block it+2, indices loaded an iteration ago
+      if (it + 3 < n_blocks) {
+        GATHER_IDX(fr, fstart, flen, fpos)                // block it+3
         advance();
       }
-    } else if (has_next) {
+    } else if (it + 2 < n_blocks) {
       FETCH(fr, fstart, flen, fpos)
       advance();
     }
@@ -360,8 +374,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
-    // the next block's rows go to the other LDS buffer while the LDS pipe is idle
-    if (has_next) { STAGE((it + 1) & 1) }
     if (n_valid < BN) {   // run tail: element v of a tile is key 8 (v >> 2) + 4 g + (v & 3)
       const int nv0 = n_valid - 4 * g, nv1 = nv0 - 32;
 #pragma unroll
@@ -371,47 +383,55 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       }
     }
 
-    // ---- online softmax: this lane's query, its 32 keys; the other 32 are in lane ^ 32
-    float mx = max3(s0[0], s1[0], s0[1]);
-    mx = max3(mx, s1[1], s0[2]);
+    // ---- softmax against a lagging row reference m_run (this lane's query, its 32 keys; the
+    // other 32 are in lane ^ 32).  The probabilities go straight to bf16 pairs in B-operand
+    // order: k slice kk covers keys [16 kk, 16 kk + 16).  The row sums are taken from the
+    // rounded pairs (v_dot2c_f32_bf16 with ones), i.e. of exactly the values the second product
+    // uses, at half the instruction count of fp32 adds.
+    const float mc = m_run * c;
+    unsigned u0[8], u1[8];
+    float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
-    for (int v = 2; v < 15; ++v) mx = max3(mx, s1[v], s0[v + 1]);
-    mx = fmaxf(mx, s1[15]);
-    mx = max_xor32(mx);
-    const float m_new = fmaxf(m_run, mx);
-    if (__any(m_new > m_run)) {
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+    for (int j = 0; j < 8; ++j) {
+      u0[j] = pack_bf16(__builtin_amdgcn_exp2f(fmaf(s0[2 * j], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s0[2 * j + 1], c, -mc)));
+      u1[j] = pack_bf16(__builtin_amdgcn_exp2f(fmaf(s1[2 * j], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s1[2 * j + 1], c, -mc)));
+      ps0 = pair_sum(u0[j], ps0);
+      ps1 = pair_sum(u1[j], ps1);
+    }
+    float ps = ps0 + ps1;
+    // Reference check: no probability exceeds its row sum, so ps <= P_MAX proves that no score
+    // of the block was more than log2(P_MAX) above the reference.  Otherwise (always for the
+    // first block, whose reference is -inf; afterwards only when a row maximum jumps) the block
+    // is redone against the true running maximum: new reference, accumulators and sum rescaled
+    // to it, probabilities recomputed from the scores.
+    if (__any(!(ps <= P_MAX))) {
+      float mx = max3(s0[0], s1[0], s0[1]);
+#pragma unroll
+      for (int v = 1; v < 15; ++v) mx = max3(mx, s1[v], s0[v + 1]);
+      mx = max_xor32(fmaxf(mx, s1[15]));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);   // 0 for the first block
+      m_run = m_new;
+      const float mc2 = m_new * c;
+      ps = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        u0[j] = pack_bf16(__builtin_amdgcn_exp2f(fmaf(s0[2 * j], c, -mc2)), __builtin_amdgcn_exp2f(fmaf(s0[2 * j + 1], c, -mc2)));
+        u1[j] = pack_bf16(__builtin_amdgcn_exp2f(fmaf(s1[2 * j], c, -mc2)), __builtin_amdgcn_exp2f(fmaf(s1[2 * j + 1], c, -mc2)));
+        ps = pair_sum(u0[j], ps);
+        ps = pair_sum(u1[j], ps);
+      }
       l_run *= alpha;
 #pragma unroll
       for (int v = 0; v < 16; ++v) { o0[v] *= alpha; o1[v] *= alpha; o2[v] *= alpha; o3[v] *= alpha; }
-      m_run = m_new;
     }
-    const float mc = m_run * c;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      s0[v] = __builtin_amdgcn_exp2f(fmaf(s0[v], c, -mc));
-      s1[v] = __builtin_amdgcn_exp2f(fmaf(s1[v], c, -mc));
-    }
-
-    // ---- P^T as B operands: k slice kk covers keys [16 kk, 16 kk + 16).  The row sums are
-    // taken from the rounded bf16 pairs (v_dot2c_f32_bf16 with ones), i.e. of exactly the
-    // values the second product uses, at half the instruction count of fp32 adds.
+    l_run += ps;
     bf16x8 pf[4];
-    float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      unsigned u0[4], u1[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        u0[j] = pack_bf16(s0[8 * h + 2 * j], s0[8 * h + 2 * j + 1]);
-        u1[j] = pack_bf16(s1[8 * h + 2 * j], s1[8 * h + 2 * j + 1]);
-        ps0 = pair_sum(u0[j], ps0);
-        ps1 = pair_sum(u1[j], ps1);
-      }
-      pf[h] = __builtin_bit_cast(bf16x8, make_uint4(u0[0], u0[1], u0[2], u0[3]));
-      pf[2 + h] = __builtin_bit_cast(bf16x8, make_uint4(u1[0], u1[1], u1[2], u1[3]));
+      pf[h] = __builtin_bit_cast(bf16x8, make_uint4(u0[4 * h], u0[4 * h + 1], u0[4 * h + 2], u0[4 * h + 3]));
+      pf[2 + h] = __builtin_bit_cast(bf16x8, make_uint4(u1[4 * h], u1[4 * h + 1], u1[4 * h + 2], u1[4 * h + 3]));
     }
-    l_run += ps0 + ps1;
 
     // ---- O^T += V^T P^T
 #pragma unroll
@@ -488,7 +508,6 @@ namespace {
 constexpr int PIPE_BUFS = 4;
 constexpr int PIPE_LDS_BYTES = PIPE_BUFS * STAGE_ELEMS * 2;
 constexpr int LEAD = 2;                  // slots between a fragment request and its use (2..6 measured alike; 2 needs the fewest registers)
-constexpr float P_MAX = 256.f;           // largest probability (relative to the row reference) the fast path accepts
 }  // namespace
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));

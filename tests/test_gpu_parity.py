@@ -201,24 +201,39 @@ def test_degenerate_cases():
     check_layer(big_tile, big_tile.fixed_routes)
 
 
-def test_row_maxima_that_jump_or_creep_late_in_the_key_stream():
-    """The pipelined kernel keeps a lagging row reference instead of the running maximum.
-    Inputs built to move the maxima late: one key far down the sequence that dominates a
-    few rows outright, and scores that rise steadily along the key axis for half the rows."""
-    cfg = small_cfg("late_max", (12, 16, 16), 4, "bf16", (4, 4, 4), (3, 3, 3), [0, 0, 2, 2], seed=23)
+@pytest.mark.parametrize("tile", [(4, 4, 4), (4, 8, 8)], ids=["tile64", "tile256"])
+def test_row_maxima_that_jump_or_creep_late_in_the_key_stream(tile):
+    """The attention kernels keep a lagging row reference instead of the running maximum.
+    Inputs built to move the maxima late: one key far down the key stream that dominates a
+    few rows outright, and scores that rise steadily along the key axis for half the rows.
+    Window heads (64-token tiles: the 128-row kernel; 256-token tiles: the pipelined one) get
+    their dominating keys at the end of the row's key set in tile order."""
+    cfg = small_cfg("late_max", (12, 16, 16), 6, "bf16", tile, (3, 3, 3), [0, 0, 2, 2, 1, 1], seed=23)
     q, k, v = make_qkv(cfg, DEV, 1)
     N, d = cfg.n_tokens, cfg.head_dim
     gen = torch.Generator(device="cpu").manual_seed(5)
     u = torch.randn(d, generator=gen)
     u = (u / u.norm()).to(DEV)
     ramp = torch.linspace(0.0, 1.0, N, device=DEV)[:, None]
+
+    def last_window_token(row, back):
+        """Token `back` places before the end of the row's key set (tile order = the order the
+        window kernels stream keys in; the mask is the oracle's)."""
+        keys = np.nonzero(vo.sta_mask_row(row, cfg.grid, cfg.tile, cfg.window))[0]
+        order = sorted(keys, key=lambda j: (vo.get_tile_id_3d(int(j), cfg.grid, cfg.tile), j))
+        return order[-1 - back]
+
     for h in range(cfg.heads):
+        r = cfg.fixed_routes[h]
         kh = k[h].float()
         # scores creep up (or down) along the keys; gentler on the core-set heads, whose pooled
         # rows are rounded to bf16 (the 2e-2 bar assumes inputs of about unit variance)
-        kh = kh + (24.0 if cfg.fixed_routes[h] == 0 else 6.0) * ramp * u[None, :]
-        for j, row in ((int(0.45 * N), 100), (int(0.93 * N), 2000), (N - 1, 7)):
-            kh[j] = (4.0 if cfg.fixed_routes[h] == 0 else 1.5) * q[h, row].float()   # a late key that dominates one row
+        kh = kh + (6.0 if r == 2 else 24.0) * ramp * u[None, :]
+        late = ((int(0.45 * N), 100), (int(0.93 * N), 2000), (N - 1, 7))
+        if r == 1:
+            late = tuple((int(last_window_token(row, back)), row) for back, row in ((0, 100), (5, 2000), (40, 7)))
+        for j, row in late:
+            kh[j] = (1.5 if r == 2 else 4.0) * q[h, row].float()   # a late key that dominates one row
         k[h] = kh.to(torch.bfloat16)
     routes = np.array(cfg.fixed_routes, dtype=np.uint8)
     plan, out = run_layer(cfg, q, k, v, routes)
@@ -226,7 +241,7 @@ def test_row_maxima_that_jump_or_creep_late_in_the_key_stream():
     for h, r in enumerate(routes):
         want = vo.head_attention(int(r), f64(q[h]), f64(k[h]), f64(v[h]), spec, None)
         err = np.abs(f64(out[h]) - want).max()
-        say(f"late_max head {h} route {r}: max-abs {err:.3e}")
+        say(f"late_max {tile} head {h} route {r}: max-abs {err:.3e}")
         assert err <= TOL["bf16"], f"head {h} route {r}: max-abs {err:.3e}"
 
 
