@@ -1,6 +1,7 @@
 // bf16 routed attention for gfx950 (CDNA4): flash-style forward.  Two kernels: a software-
-// pipelined one for the dense and core-set segments (further down) and a simpler one for the
-// window segment (first).  Common to both:
+// pipelined one (further down) that runs every segment of the layer call -- dense, core-set
+// and, gathering rows through the tile permutation, the window tiles -- and a simpler one
+// (first) for window tiles given as tile-ordered copies.  Common to both:
 //
 // A wavefront owns 32 query rows; keys stream through LDS in blocks of 64 rows.  Both contractions run on
 // v_mfma_f32_32x32x16_bf16 and are computed TRANSPOSED so that a lane owns one query:
@@ -113,13 +114,13 @@ struct RunList {
   __device__ __forceinline__ int len(int r) const { return runs ? runs[2 * r + 1] : single_len; }
 };
 
-// Rows of keys j0 + step i (i < NR) of the 64-key block that begins pos keys into run r, whose
+// Rows of keys j0 + step i (i < NR) of the bn-key block that begins pos keys into run r, whose
 // first row is s and whose length is len (r, pos, s, len wave-uniform; j0 per lane).  A block
 // that reaches past the end of run r continues in the following runs: they are walked with
 // uniform control flow, each lane keeping the row of the run its key falls in.  Keys past the
 // end of the last run repeat its last row (they are masked out of the softmax).
 template <int NR>
-__device__ __forceinline__ void block_rows(const RunList& rl, int r, int pos, int s, int len, int j0, int step,
+__device__ __forceinline__ void block_rows(const RunList& rl, int r, int pos, int s, int len, int bn, int j0, int step,
                                            int (&rows)[NR]) {
   int k[NR];
 #pragma unroll
@@ -127,7 +128,7 @@ __device__ __forceinline__ void block_rows(const RunList& rl, int r, int pos, in
     k[i] = pos + j0 + step * i;
     rows[i] = s + min(k[i], len - 1);
   }
-  int end = pos + BN;
+  int end = pos + bn;
   while (end > len && r + 1 < rl.n_runs) {
     end -= len;
 #pragma unroll
@@ -158,19 +159,17 @@ __device__ unsigned g_dbg_stamps[18];
 #define DBG_CLK_END(cond_)
 #endif
 
-// GATHER: the item's rows are tile-order indices into the caller's tensors -- every query,
-// key, value and output row goes through a.tok_of (tile-order index -> token index) instead
-// of living in tile-ordered copies.  The indices of a key block are loaded one block ahead of
-// its rows, so the two dependent loads never wait for each other inside one iteration.
-template <int NW, bool GATHER>   // NW wavefronts per workgroup: 4 (two workgroups per CU) or 8 (one)
+// Window segment over tile-ordered copies of Q, K, V (the staged call with q_t, k_t, v_t, o_t
+// given): a tile's key set is a short list of runs of consecutive rows.
+template <int NW>   // NW wavefronts per workgroup: 4 (two workgroups per CU)
 __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   constexpr int STG_ROWS = 4 * NW, STG_PASSES = BN / STG_ROWS;   // staging: rows per pass, passes per block
   const WorkItem w = decode_item<32 * NW, D>(a, xcd_item(blockIdx.x, gridDim.x, NW == 4));
-  const uint16_t* Q = (const uint16_t*)(w.seg == 0 || GATHER ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
-  const uint16_t* K = (const uint16_t*)(w.seg == 0 || GATHER ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
-  const uint16_t* V = (const uint16_t*)(w.seg == 0 || GATHER ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
-  uint16_t* O = (uint16_t*)(w.seg == 0 || GATHER ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
+  const uint16_t* Q = (const uint16_t*)(w.seg == 0 ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
+  const uint16_t* K = (const uint16_t*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
+  const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
+  uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
   const unsigned row_stride = (unsigned)w.row_stride;   // rows * stride < 2^31 elements (checked on the host)
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -180,8 +179,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   // Q^T fragments: lane = query (l32), 8 consecutive dims per 16-wide k slice
   bf16x8 qf[8];
   {
-    unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
-    if (GATHER) qrow = (unsigned)a.tok_of[qrow];
+    const unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
     const uint16_t* qp = Q + qrow * row_stride + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * ks));
@@ -219,7 +217,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
     }                                                                                      \
   } else {                                                                                 \
     int rows_[STG_PASSES];                                                                 \
-    block_rows<STG_PASSES>(rl, run_, pos_, start_, len_, ld_row, STG_ROWS, rows_);         \
+    block_rows<STG_PASSES>(rl, run_, pos_, start_, len_, BN, ld_row, STG_ROWS, rows_);         \
     FETCH_TAIL(kr0, vr0, rows_[0])                                                         \
     FETCH_TAIL(kr1, vr1, rows_[1])                                                         \
     if constexpr (STG_PASSES == 4) {                                                       \
@@ -242,32 +240,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       *(uint4*)(vb_ + 3 * STG_ROWS * VSTR) = vr3;                         \
     }                                                                     \
   }
-  // GATHER: token index of staging row i of a block, and the loads of that row
-  int gi0 = 0, gi1 = 0, gi2 = 0, gi3 = 0;
-#define GATHER_IDX(run_, start_, len_, pos_)                                               \
-  {                                                                                        \
-    int rows_[STG_PASSES];                                                                 \
-    block_rows<STG_PASSES>(rl, run_, pos_, start_, len_, ld_row, STG_ROWS, rows_);         \
-    gi0 = a.tok_of[rows_[0]];                                                              \
-    gi1 = a.tok_of[rows_[1]];                                                              \
-    if constexpr (STG_PASSES == 4) {                                                       \
-      gi2 = a.tok_of[rows_[2]];                                                            \
-      gi3 = a.tok_of[rows_[3]];                                                            \
-    }                                                                                      \
-  }
-#define GATHER_ROW(kr_, vr_, gi_)                                        \
-  {                                                                      \
-    const unsigned off_ = (unsigned)(gi_) * row_stride + ld_col;         \
-    kr_ = *(const uint4*)(K + off_);                                     \
-    vr_ = *(const uint4*)(V + off_);                                     \
-  }
-#define GATHER_ROWS()                 \
-  GATHER_ROW(kr0, vr0, gi0)           \
-  GATHER_ROW(kr1, vr1, gi1)           \
-  if constexpr (STG_PASSES == 4) {    \
-    GATHER_ROW(kr2, vr2, gi2)         \
-    GATHER_ROW(kr3, vr3, gi3)         \
-  }
   const RunList rl(w);
   auto run_start = [&](int r) { return rl.start(r); };
   auto run_len = [&](int r) { return rl.len(r); };
@@ -282,8 +254,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   float m_run = -INFINITY, l_run = 0.f;
   const float c = a.scale * 1.4426950408889634f;
 
-  // fetch cursor (run, offset in it, its first row and length): the next block to request --
-  // its rows, or with GATHER its token indices (the rows follow one iteration later)
+  // fetch cursor (run, offset in it, its first row and length): the next block to request
   int fr = 0, fpos = 0, fstart = run_start(0), flen = run_len(0), left = n_keys;
   auto advance = [&]() {
     fpos += BN;
@@ -294,31 +265,15 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       flen = run_len(fr);
     }
   };
-  // Prologue: block 0 goes to LDS, the rows of block 1 wait in the staging registers (and with
-  // GATHER the indices of block 2 in gi*).  Iteration it then writes block it + 1 to the other
-  // buffer first thing and requests block it + 2, so a row has a whole iteration to arrive.
-  if constexpr (GATHER) {
-    GATHER_IDX(fr, fstart, flen, fpos)
-    advance();
-    GATHER_ROWS()
-    if (n_blocks > 1) {
-      GATHER_IDX(fr, fstart, flen, fpos)
-      advance();
-    }
-    STAGE(0)
-    if (n_blocks > 1) { GATHER_ROWS() }
-    if (n_blocks > 2) {
-      GATHER_IDX(fr, fstart, flen, fpos)
-      advance();
-    }
-  } else {
+  // Prologue: block 0 goes to LDS, the rows of block 1 wait in the staging registers.  Iteration
+  // it then writes block it + 1 to the other buffer first thing and requests block it + 2, so
+  // a row has a whole iteration to arrive.
+  FETCH(fr, fstart, flen, fpos)
+  advance();
+  STAGE(0)
+  if (n_blocks > 1) {
     FETCH(fr, fstart, flen, fpos)
     advance();
-    STAGE(0)
-    if (n_blocks > 1) {
-      FETCH(fr, fstart, flen, fpos)
-      advance();
-    }
   }
   __syncthreads();
 
@@ -329,13 +284,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 
   for (int it = 0; it < n_blocks; ++it) {
     if (it + 1 < n_blocks) { STAGE((it + 1) & 1) }        // rows requested an iteration ago
-    if constexpr (GATHER) {
-      if (it + 2 < n_blocks) { GATHER_ROWS() }            // block it+2, indices loaded an iteration ago
-      if (it + 3 < n_blocks) {
-        GATHER_IDX(fr, fstart, flen, fpos)                // block it+3
-        advance();
-      }
-    } else if (it + 2 < n_blocks) {
+    if (it + 2 < n_blocks) {
       FETCH(fr, fstart, flen, fpos)
       advance();
     }
@@ -463,31 +412,21 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
     u.y = pack_bf16(acc_[4 * q4 + 2] * inv, acc_[4 * q4 + 3] * inv);                 \
     *(uint2*)(st + l32 * LSTR + 32 * (dt_) + 8 * q4 + 4 * g) = u;                    \
   }
-  // output rows of this lane (row (lane >> 4) + 4 i of the wavefront's 32): looked up together,
-  // ahead of the barrier, so the stores below do not wait for one lookup each
-  unsigned orow[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    orow[i] = w.row0 + min(32 * wave + (lane >> 4) + 4 * i, w.n_rows - 1);
-    if (GATHER) orow[i] = (unsigned)a.tok_of[orow[i]];
-  }
   STORE_TILE(0, o0) STORE_TILE(1, o1) STORE_TILE(2, o2) STORE_TILE(3, o3)
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int row = (lane >> 4) + 4 * i;
     if (32 * wave + row < w.n_rows)
-      *(uint4*)(O + orow[i] * row_stride + (lane & 15) * 8) = *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+      *(uint4*)(O + (unsigned)(w.row0 + 32 * wave + row) * row_stride + (lane & 15) * 8) =
+          *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
   }
 }
-#undef GATHER_IDX
-#undef GATHER_ROW
-#undef GATHER_ROWS
 
 
 // ------------------------------------------------------------------------------------------
-// Software-pipelined kernel for the dense and core-set segments (8 wavefronts, 256 query
-// rows, one workgroup per CU).  Every matrix instruction gets independent vector work to run
+// Software-pipelined kernel (described for its main form: 8 wavefronts, 256 query rows, 64-key
+// blocks, one workgroup per CU).  Every matrix instruction gets independent vector work to run
 // in its shadow, inside the same wavefront:
 //
 //   iteration i:   matrix pipe   O^T += V^T(i-1) P^T(i-1)   then   S^T(i+1) = K(i+1) Q^T
@@ -506,7 +445,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 // ------------------------------------------------------------------------------------------
 namespace {
 constexpr int PIPE_BUFS = 4;
-constexpr int PIPE_LDS_BYTES = PIPE_BUFS * STAGE_ELEMS * 2;
+constexpr int PIPE_LDS_BYTES = PIPE_BUFS * STAGE_ELEMS * 2;       // 8 wavefronts, 64-key stages
+constexpr int PIPE4_LDS_BYTES = PIPE_BUFS * (STAGE_ELEMS / 2) * 2;   // 4 wavefronts, 32-key stages
 constexpr int LEAD = 2;                  // slots between a fragment request and its use (2..6 measured alike; 2 needs the fewest registers)
 }  // namespace
 
@@ -515,15 +455,28 @@ typedef __attribute__((address_space(3))) u32x4* lds_u4_wptr;
 
 __device__ __forceinline__ float elem_of(const f32x16& t0, const f32x16& t1, int e) { return e < 16 ? t0[e] : t1[e - 16]; }
 
-// WIN: window items read through the tile permutation (see the GATHER flag of the window kernel
-// above): rows of the item are tile-order indices, translated by a.tok_of; the key rows are the
-// concatenation of the tile's runs cut into 64-key blocks.  Used when a tile has more than 128
-// tokens, i.e. fills more than half of a 256-row workgroup.
-template <bool WIN>
-__global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a) {
+// WIN: window items read through the tile permutation: the item's rows are tile-order indices
+// into the caller's tensors -- every query, key, value and output row goes through a.tok_of
+// (tile-order index -> token index) instead of living in tile-ordered copies; the key rows are
+// the concatenation of the tile's runs cut into blocks.  The token indices of a key block are
+// looked up one block ahead of its rows, so the two dependent loads never wait for each other
+// inside one iteration.
+// NWV: wavefronts per workgroup.  8: 256 query rows, 64-key blocks, one workgroup per CU (dense,
+// core-set, window tiles of more than 128 tokens).  4: 128 query rows, 32-key blocks, half the
+// ring, two workgroups per CU (smaller window tiles): the iteration has 16 slots instead of 32.
+template <bool WIN, int NWV>
+__global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  constexpr int STG_ROWS = 32;
-  const WorkItem w = decode_item<BM_LONG, D>(a, xcd_item(blockIdx.x, gridDim.x, WIN));
+  constexpr int KB = 8 * NWV;               // keys per block: 64 (8 wavefronts) or 32 (4)
+  constexpr int NS = KB / 2;                // slots = matrix instructions per iteration
+  constexpr int NPV = NS / 2;               // of which second-product slots (then NS - NPV score slots)
+  constexpr int NE = KB / 2;                // score elements per lane and block
+  constexpr int NP = NE / 2;                // bf16 pairs of probabilities per lane and block
+  constexpr int NKS = KB / 16;              // 16-key k slices of the second product
+  constexpr int STG_ROWS = KB / 2;          // a thread stages rows (tid >> 4) and (tid >> 4) + STG_ROWS
+  constexpr int STAGE_ELEMS = KB * (LSTR + VSTR), KTILE = KB * LSTR;   // one ring stage: K block, V block
+  static_assert(NWV == 8 || NWV == 4, "8 wavefronts x 64-key blocks or 4 wavefronts x 32-key blocks");
+  const WorkItem w = decode_item<32 * NWV, D>(a, xcd_item(blockIdx.x, gridDim.x, WIN));
   const uint16_t* Q = (const uint16_t*)(w.seg == 0 || WIN ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
   const uint16_t* K = (const uint16_t*)(w.seg == 0 || WIN ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
   const uint16_t* V = (const uint16_t*)(w.seg == 0 || WIN ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
@@ -550,7 +503,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
   auto run_len = [&](int r) { return rl.len(r); };
   int n_keys = 0;
   for (int r = 0; r < w.n_runs; ++r) n_keys += run_len(r);
-  const int n_blocks = (n_keys + BN - 1) / BN;   // dense / core-set: one run
+  const int n_blocks = (n_keys + KB - 1) / KB;   // dense / core-set: one run
 
   // ---- global -> register -> LDS staging: thread moves the 16-byte chunk (tid & 15) of rows
   // (tid >> 4) and (tid >> 4) + 32 of K and of V.  The fetch stream walks the run list one
@@ -563,8 +516,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
   auto fetch_cursor = [&]() {      // first row and last valid row offset of the block, then advance
     f_row0 = (unsigned)(fstart + fpos);
     f_lim = (unsigned)(flen - 1 - fpos);
-    if (fpos + BN < flen) {
-      fpos += BN;
+    if (fpos + KB < flen) {
+      fpos += KB;
     } else if (fr + 1 < w.n_runs) {
       ++fr;
       fpos = 0;
@@ -594,7 +547,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     wi_pos = fpos;
     wi_start = fstart;
     wi_len = flen;
-    fpos += BN;
+    fpos += KB;
     while (fpos >= flen && fr + 1 < w.n_runs) {
       fpos -= flen;
       ++fr;
@@ -604,7 +557,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
   };
   auto win_idx = [&]() {           // token indices of the noted block
     int rows[2];
-    block_rows<2>(rl, wi_run, wi_pos, wi_start, wi_len, ld_row, STG_ROWS, rows);
+    block_rows<2>(rl, wi_run, wi_pos, wi_start, wi_len, KB, ld_row, STG_ROWS, rows);
     gi0 = a.tok_of[rows[0]];
     gi1 = a.tok_of[rows[1]];
   };
@@ -628,14 +581,14 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
   int cr = 0, cpos = 0, clen = flen, cblk = 0;
   auto next_valid = [&]() {      // 0 past the last block: a block of masked keys adds nothing
     if constexpr (WIN) {
-      const int nv = min(BN, max(0, n_keys - BN * cblk));
+      const int nv = min(KB, max(0, n_keys - KB * cblk));
       ++cblk;
       return nv;
     }
-    const int nv = cblk < n_blocks ? min(BN, clen - cpos) : 0;
+    const int nv = cblk < n_blocks ? min(KB, clen - cpos) : 0;
     ++cblk;
-    if (cpos + BN < clen) {
-      cpos += BN;
+    if (cpos + KB < clen) {
+      cpos += KB;
     } else if (cr + 1 < w.n_runs) {
       ++cr;
       cpos = 0;
@@ -667,9 +620,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
   }
   float m_ref = -INFINITY, l_run = 0.f;   // row reference (a lagging running maximum) and row sum
   const float c = a.scale * 1.4426950408889634f;
-  bf16x8 pa[4], pb[4];
+  bf16x8 pa[NKS], pb[NKS];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) pa[i] = pb[i] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+  for (int i = 0; i < NKS; ++i) pa[i] = pb[i] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
 
   // element v of a 32-key score tile is key 8 (v >> 2) + 4 g + (v & 3)
   auto mask_tail = [&](f32x16& t0, f32x16& t1, int n_valid) {
@@ -677,7 +630,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       if (8 * (v >> 2) + (v & 3) >= nv0) t0[v] = -INFINITY;
-      if (8 * (v >> 2) + (v & 3) >= nv1) t1[v] = -INFINITY;
+      if (KB == 64 && 8 * (v >> 2) + (v & 3) >= nv1) t1[v] = -INFINITY;
     }
   };
 
@@ -685,11 +638,11 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
     sa0 = MFMA(lds_frag3(k_rd + 16 * ks), qf[ks], sa0);
-    sa1 = MFMA(lds_frag3(k_rd + 32 * LSTR + 16 * ks), qf[ks], sa1);
+    if constexpr (KB == 64) sa1 = MFMA(lds_frag3(k_rd + 32 * LSTR + 16 * ks), qf[ks], sa1);
   }
   {
     const int nv = next_valid();
-    if (nv < BN) mask_tail(sa0, sa1, nv);
+    if (nv < KB) mask_tail(sa0, sa1, nv);
   }
 
 #define SLOT_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -706,15 +659,15 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
 #endif
   // One iteration.  sc*: scores of block i (in), sn*: scores of block i+1 (out),
   // pp: P^T(i-1) (in), pc: P^T(i) (out).
-  auto body = [&](int i, f32x16& sc0, f32x16& sc1, f32x16& sn0, f32x16& sn1, bf16x8 (&pp)[4], bf16x8 (&pc)[4]) {
+  auto body = [&](int i, f32x16& sc0, f32x16& sc1, f32x16& sn0, f32x16& sn1, bf16x8 (&pp)[NKS], bf16x8 (&pc)[NKS]) {
     const lds_ptr vq = opaque(v_rd + ((i ? i - 1 : 0) & 3) * STAGE_ELEMS);
     const lds_ptr kq = opaque(k_rd + ((i + 1) & 3) * STAGE_ELEMS);
     const int wbuf = (i + 2) & 3;
     if constexpr (WIN) win_at();                     // block i+4: its token indices are looked up in slot 27
     else fetch_cursor();                             // block i+3 (scalar work and branches: before the slots)
-    bf16x8 vf[16], kf[16];
+    bf16x8 vf[NPV], kf[NS - NPV];
     auto v_req = [&](int n) { vf[n] = v_frag(vq, n); };
-    auto k_req = [&](int n) { kf[n] = lds_frag3(kq + 32 * (n & 1) * LSTR + 16 * (n >> 1)); };
+    auto k_req = [&](int n) { kf[n] = lds_frag3(KB == 64 ? kq + 32 * (n & 1) * LSTR + 16 * (n >> 1) : kq + 16 * n); };
 #ifdef PIPE_STAMPS
     unsigned long long ts0, ts1, ts2, ts3, ts4, ts5;
     asm volatile("s_memtime %0" : "=s"(ts0));
@@ -723,39 +676,43 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
 #pragma unroll
     for (int n = 0; n < LEAD; ++n) vf[n] = vpre[n];
     float ps0 = 0.f, ps1 = 0.f;
-    float x[32], ex[32];
-    unsigned u[2][8];
+    float x[NE], ex[NE];
+    unsigned u[2][8];                  // pair p of the block is u[p >> 3][p & 7]
     const float mc = m_ref * c;
     unsigned off0 = 0, off1 = 0;
 #pragma unroll
-    for (int n = 0; n < 32; ++n) {
+    for (int n = 0; n < NS; ++n) {
       SLOT_FENCE();
 #ifdef PIPE_STAMPS
       if (n == 1) asm volatile("s_memtime %0" : "=s"(ts1));
-      if (n == 8) asm volatile("s_memtime %0" : "=s"(ts2));
-      if (n == 16) asm volatile("s_memtime %0" : "=s"(ts3));
-      if (n == 24) asm volatile("s_memtime %0" : "=s"(ts4));
+      if (n == NS / 4) asm volatile("s_memtime %0" : "=s"(ts2));
+      if (n == NS / 2) asm volatile("s_memtime %0" : "=s"(ts3));
+      if (n == 3 * NS / 4) asm volatile("s_memtime %0" : "=s"(ts4));
 #endif
       // ---- matrix instruction of the slot
-      if (n < 16) {
+      if (n < NPV) {
         o[n & 3] = MFMA(vf[n], pp[n >> 2], o[n & 3]);
       } else {
-        const int m = n - 16;
+        const int m = n - NPV;
         if (m == 0) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) sn0[v] = 0.f;
         }
-        if (m == 1) {
+        if (KB == 64 && m == 1) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) sn1[v] = 0.f;
         }
-        if (m & 1) sn1 = MFMA(kf[m], qf[m >> 1], sn1);
-        else sn0 = MFMA(kf[m], qf[m >> 1], sn0);
+        if constexpr (KB == 64) {      // two key tiles, alternating
+          if (m & 1) sn1 = MFMA(kf[m], qf[m >> 1], sn1);
+          else sn0 = MFMA(kf[m], qf[m >> 1], sn0);
+        } else {
+          sn0 = MFMA(kf[m], qf[m], sn0);
+        }
       }
       // ---- fragment requests for the slot LEAD ahead
-      if (n + LEAD < 16) v_req(n + LEAD);
-      else if (n + LEAD < 32) k_req(n + LEAD - 16);
-      else vpre[n + LEAD - 32] = v_frag(vq_next, n + LEAD - 32);
+      if (n + LEAD < NPV) v_req(n + LEAD);
+      else if (n + LEAD < NS) k_req(n + LEAD - NPV);
+      else vpre[n + LEAD - NS] = v_frag(vq_next, n + LEAD - NS);
       // ---- vector work in the shadow of the matrix instruction: the probabilities of block i
       // relative to the row reference m_ref, spread evenly over the slots and staggered by
       // stage so that no instruction of a slot waits for another one of the same slot (a
@@ -764,9 +721,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
       // Element e < 16 is sc0[e], element e >= 16 is sc1[e - 16]; pair p = elements 2p, 2p+1.
       auto elem = [&](int e) { return e < 16 ? sc0[e] : sc1[e - 16]; };
       if (n == 0) { x[0] = fmaf(elem(0), c, -mc); x[1] = fmaf(elem(1), c, -mc); }
-      if (n >= 1 && n <= 30) x[n + 1] = fmaf(elem(n + 1), c, -mc);
-      if (n >= 1 && n <= 30) ex[n - 1] = __builtin_amdgcn_exp2f(x[n - 1]);
-      if (n == 31) { ex[30] = __builtin_amdgcn_exp2f(x[30]); ex[31] = __builtin_amdgcn_exp2f(x[31]); }
+      if (n >= 1 && n <= NS - 2) x[n + 1] = fmaf(elem(n + 1), c, -mc);
+      if (n >= 1 && n <= NS - 2) ex[n - 1] = __builtin_amdgcn_exp2f(x[n - 1]);
+      if (n == NS - 1) { ex[NE - 2] = __builtin_amdgcn_exp2f(x[NE - 2]); ex[NE - 1] = __builtin_amdgcn_exp2f(x[NE - 1]); }
       if (n >= 3 && (n & 1)) {
         const int p = (n - 3) >> 1;
         u[p >> 3][p & 7] = pack_bf16(ex[2 * p], ex[2 * p + 1]);
@@ -777,27 +734,30 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
         if (p >> 3) ps1 = pair_sum(u[1][p & 7], ps1);
         else ps0 = pair_sum(u[0][p & 7], ps0);
       }
-      if (n == 22) {                                 // block i+3: addresses, then one load per slot
+      // ---- staging: block i+2 leaves the registers (slots SW..SW+3), block i+3 enters (addresses
+      // in slot SL, one load in each of the next four), the indices of block i+4 follow (slot SI)
+      constexpr int SW = NS == 32 ? 12 : 4, SL = NS == 32 ? 22 : 9, SI = NS == 32 ? 27 : 14;
+      if (n == SL) {
         off0 = WIN ? win_off(gi0) : row_off(0);
         off1 = WIN ? win_off(gi1) : row_off(1);
       }
-      if (WIN && n == 27) win_idx();                 // block i+4
-      // ---- staging: block i+2 leaves the registers (slots 12-15), block i+3 enters (23-26)
-      if (n == 12) k_wr[(wbuf * STAGE_ELEMS) / 8] = kr0;
-      if (n == 13) k_wr[(wbuf * STAGE_ELEMS + STG_ROWS * LSTR) / 8] = kr1;
-      if (n == 14) v_wr[(wbuf * STAGE_ELEMS) / 8] = vr0;
-      if (n == 15) v_wr[(wbuf * STAGE_ELEMS + STG_ROWS * VSTR) / 8] = vr1;
-      if (n == 23) kr0 = ld16(K, off0);
-      if (n == 24) vr0 = ld16(V, off0);
-      if (n == 25) kr1 = ld16(K, off1);
-      if (n == 26) vr1 = ld16(V, off1);
+      if (WIN && n == SI) win_idx();
+      if (n == SW) k_wr[(wbuf * STAGE_ELEMS) / 8] = kr0;
+      if (n == SW + 1) k_wr[(wbuf * STAGE_ELEMS + STG_ROWS * LSTR) / 8] = kr1;
+      if (n == SW + 2) v_wr[(wbuf * STAGE_ELEMS) / 8] = vr0;
+      if (n == SW + 3) v_wr[(wbuf * STAGE_ELEMS + STG_ROWS * VSTR) / 8] = vr1;
+      if (n == SL + 1) kr0 = ld16(K, off0);
+      if (n == SL + 2) vr0 = ld16(V, off0);
+      if (n == SL + 3) kr1 = ld16(K, off1);
+      if (n == SL + 4) vr1 = ld16(V, off1);
     }
     SLOT_FENCE();
-    u[1][7] = pack_bf16(ex[30], ex[31]);
-    ps1 = pair_sum(u[1][6], ps1);
-    ps1 = pair_sum(u[1][7], ps1);
+    constexpr int LP = NP - 1;         // last pair: packed here, and the last two pairs summed
+    u[LP >> 3][LP & 7] = pack_bf16(ex[NE - 2], ex[NE - 1]);
+    ps1 = pair_sum(u[LP >> 3][(LP - 1) & 7], ps1);
+    ps1 = pair_sum(u[LP >> 3][LP & 7], ps1);
     float ps = ps0 + ps1;
-    asm volatile("" : "+v"(u[1][7]), "+v"(ps));
+    asm volatile("" : "+v"(u[LP >> 3][LP & 7]), "+v"(ps));
 #ifdef PIPE_STAMPS
     asm volatile("s_memtime %0" : "=s"(ts5));
 #endif
@@ -816,17 +776,26 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     // block is redone against the true running maximum: new reference, accumulators and sum
     // rescaled to it, probabilities recomputed from the scores, which are still in registers.
     if (__any(!(ps <= P_MAX))) {
-      float mx = max3(sc0[0], sc1[0], sc0[1]);
+      float mx;
+      if constexpr (KB == 64) {
+        mx = max3(sc0[0], sc1[0], sc0[1]);
 #pragma unroll
-      for (int k = 1; k < 15; ++k) mx = max3(mx, sc1[k], sc0[k + 1]);
-      mx = max_xor32(fmaxf(mx, sc1[15]));
+        for (int k = 1; k < 15; ++k) mx = max3(mx, sc1[k], sc0[k + 1]);
+        mx = fmaxf(mx, sc1[15]);
+      } else {
+        mx = max3(sc0[0], sc0[1], sc0[2]);
+#pragma unroll
+        for (int k = 3; k < 15; k += 2) mx = max3(mx, sc0[k], sc0[k + 1]);
+        mx = fmaxf(mx, sc0[15]);
+      }
+      mx = max_xor32(mx);
       const float m_new = fmaxf(m_ref, mx);
       const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);     // 0 for the first block
       m_ref = m_new;
       const float mc2 = m_new * c;
       ps = 0.f;
 #pragma unroll
-      for (int p = 0; p < 16; ++p) {
+      for (int p = 0; p < NP; ++p) {
         const float e0 = __builtin_amdgcn_exp2f(fmaf(elem_of(sc0, sc1, 2 * p), c, -mc2));
         const float e1 = __builtin_amdgcn_exp2f(fmaf(elem_of(sc0, sc1, 2 * p + 1), c, -mc2));
         u[p >> 3][p & 7] = pack_bf16(e0, e1);
@@ -842,10 +811,11 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       pc[h] = __builtin_bit_cast(bf16x8, make_uint4(u[0][4 * h], u[0][4 * h + 1], u[0][4 * h + 2], u[0][4 * h + 3]));
-      pc[2 + h] = __builtin_bit_cast(bf16x8, make_uint4(u[1][4 * h], u[1][4 * h + 1], u[1][4 * h + 2], u[1][4 * h + 3]));
+      if constexpr (KB == 64)
+        pc[2 + h] = __builtin_bit_cast(bf16x8, make_uint4(u[1][4 * h], u[1][4 * h + 1], u[1][4 * h + 2], u[1][4 * h + 3]));
     }
     const int nv = next_valid();
-    if (nv < BN) mask_tail(sn0, sn1, nv);
+    if (nv < KB) mask_tail(sn0, sn1, nv);
   };
   // An even number of iterations, so the two register sets swap back; when the block count
   // is odd the last iteration works on a block of masked keys (probabilities 0) and only its
@@ -872,13 +842,13 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_pipe_kernel(const AttnArgs a
     const int last = ((n_blocks + 1) & ~1) - 1;
     const lds_ptr vq = opaque(v_rd + (last & 3) * STAGE_ELEMS);
 #pragma unroll
-    for (int n = 0; n < 16; ++n)
+    for (int n = 0; n < NPV; ++n)
       o[n & 3] = MFMA(n < LEAD ? vpre[n] : v_frag(vq, n), pa[n >> 2], o[n & 3]);
   }
   DBG_CLK_END(true)
 #ifdef PIPE_STAMPS
-  if (blockIdx.x == 300 && lane == 0 && (wave == 0 || wave == 4 || wave == 7))
-    for (int k = 0; k < 6; ++k) g_dbg_stamps[(wave == 0 ? 0 : wave == 4 ? 1 : 2) * 6 + k] = stamp_acc[k];
+  if (blockIdx.x == 300 && lane == 0 && (wave == 0 || wave == NWV / 2 || wave == NWV - 1))
+    for (int k = 0; k < 6; ++k) g_dbg_stamps[(wave == 0 ? 0 : wave == NWV / 2 ? 1 : 2) * 6 + k] = stamp_acc[k];
 #endif
   __syncthreads();   // every wavefront is done with the ring before stage 0 is reused below
 
@@ -912,10 +882,10 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   static std::once_flag once;
   static int attr_rc = VORTA_OK;
   std::call_once(once, [] {
-    attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4, false>, "attn_bf16_kernel<4, false>", LDS_BYTES);
-    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4, true>, "attn_bf16_kernel<4, true>", LDS_BYTES);
-    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<false>, "attn_bf16_pipe_kernel<false>", PIPE_LDS_BYTES);
-    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true>, "attn_bf16_pipe_kernel<true>", PIPE_LDS_BYTES);
+    attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4>, "attn_bf16_kernel<4>", LDS_BYTES);
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<false, 8>, "attn_bf16_pipe_kernel<false, 8>", PIPE_LDS_BYTES);
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true, 8>, "attn_bf16_pipe_kernel<true, 8>", PIPE_LDS_BYTES);
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true, 4>, "attn_bf16_pipe_kernel<true, 4>", PIPE4_LDS_BYTES);
   });
   if (attr_rc) return attr_rc;
   // Long items -- dense heads, core-set heads and the text rows of the window heads, which
@@ -928,21 +898,22 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
     // the last items (at most one per two CUs) go out as half-row items: see AttnArgs::split_from
     const int n_split = std::min(a.end_tile, p->n_cus / 2);
     a.split_from = a.end_tile - n_split;
-    hipLaunchKernelGGL(attn_bf16_pipe_kernel<false>, dim3(a.end_tile + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
+    hipLaunchKernelGGL((attn_bf16_pipe_kernel<false, 8>), dim3(a.end_tile + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
   }
-  // Window tiles: tiles of more than 128 tokens fill a 256-row workgroup well enough for the
-  // pipelined kernel (it needs the gather form); smaller tiles get one 128-row workgroup each
-  const bool win_pipe = io->q_t == nullptr && p->tile_tokens > BM;
-  if (int rc = fill_attn_args(p, win_rl, io, win_pipe ? BM_LONG : BM, WIN_TILES, &a)) return rc;
-  if (a.end_tile > 0 && win_pipe) {
+  // Window tiles.  Gathered from the caller's tensors (no tile-ordered copies given): the
+  // pipelined kernel again -- tiles of more than 128 tokens in 256-row workgroups of 8
+  // wavefronts, smaller tiles in 128-row workgroups of 4 wavefronts on 32-key blocks, two per CU.
+  // Over tile-ordered copies: the plain 128-row kernel.
+  const bool win_long = a.win_gather && p->tile_tokens > BM;
+  if (int rc = fill_attn_args(p, win_rl, io, win_long ? BM_LONG : BM, WIN_TILES, &a)) return rc;
+  if (a.end_tile > 0 && win_long) {
     const int n_split = std::min(a.end_tile, p->n_cus / 2);
     a.split_from = a.end_tile - n_split;
-    hipLaunchKernelGGL(attn_bf16_pipe_kernel<true>, dim3(a.end_tile + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
+    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 8>), dim3(a.end_tile + n_split), dim3(512), PIPE_LDS_BYTES, (hipStream_t)stream, a);
+  } else if (a.end_tile > 0 && a.win_gather) {
+    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 4>), dim3(a.end_tile), dim3(256), PIPE4_LDS_BYTES, (hipStream_t)stream, a);
   } else if (a.end_tile > 0) {
-    if (a.win_gather)
-      hipLaunchKernelGGL((attn_bf16_kernel<4, true>), dim3(a.end_tile), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
-    else
-      hipLaunchKernelGGL((attn_bf16_kernel<4, false>), dim3(a.end_tile), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+    hipLaunchKernelGGL((attn_bf16_kernel<4>), dim3(a.end_tile), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(VORTA_EHIP, "launch of attn_bf16 kernels: %s", hipGetErrorString(e));
