@@ -181,6 +181,15 @@ def test_seeded_random_small_layers(seed):
     check_layer(cfg, routes, layout=int(rng.integers(0, 2)), center_mode=int(rng.integers(0, 2)))
 
 
+@pytest.mark.parametrize("n_text,layout", [(300, 1), (515, 0)])
+def test_text_rows_spanning_several_query_blocks(n_text, layout):
+    """Text rows of a window head attend to every row and run as long items of the pipelined
+    kernel, next to the dense heads: more text rows than one 256-row item holds, a ragged last
+    item, and (the grid being small) every item issued as two half-row items."""
+    cfg = small_cfg(f"text{n_text}", (4, 6, 8), 4, "bf16", (2, 3, 4), (3, 3, 3), [1, 0, 2, 1], n_text=n_text, seed=31)
+    check_layer(cfg, cfg.fixed_routes, layout=layout)
+
+
 def test_window_identity_centres_and_wide_windows():
     cfg = small_cfg("ident", (4, 8, 8), 2, "bf16", (2, 2, 2), (1, 3, 5), [1, 1])
     check_layer(cfg, cfg.fixed_routes, center_mode=1)
