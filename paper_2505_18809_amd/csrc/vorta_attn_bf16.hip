@@ -142,22 +142,6 @@ __device__ __forceinline__ void block_rows(const RunList& rl, int r, int pos, in
   }
 }
 
-#ifdef VORTA_DEBUG_CLOCKS
-__device__ long long g_dbg_clk[16];
-__device__ unsigned g_dbg_stamps[18];
-#define DBG_CLK_BEGIN const long long dbg_c0 = __builtin_amdgcn_s_memtime(), dbg_r0 = __builtin_amdgcn_s_memrealtime();
-#define DBG_CLK_END(cond_)                                              \
-  if ((cond_) && threadIdx.x == 0 && (blockIdx.x == 300 || blockIdx.x == 1500 || blockIdx.x == 3000 || blockIdx.x == 4100)) { \
-    const int s_ = blockIdx.x == 300 ? 0 : blockIdx.x == 1500 ? 4 : blockIdx.x == 3000 ? 8 : 12;   \
-    g_dbg_clk[s_] = __builtin_amdgcn_s_memtime() - dbg_c0;               \
-    g_dbg_clk[s_ + 1] = __builtin_amdgcn_s_memrealtime() - dbg_r0;       \
-    g_dbg_clk[s_ + 2] = n_blocks;                                        \
-    g_dbg_clk[s_ + 3] = dbg_r0;                                          \
-  }
-#else
-#define DBG_CLK_BEGIN
-#define DBG_CLK_END(cond_)
-#endif
 
 // Window segment over tile-ordered copies of Q, K, V (the staged call with q_t, k_t, v_t, o_t
 // given): a tile's key set is a short list of runs of consecutive rows.
@@ -174,7 +158,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
-  DBG_CLK_BEGIN
 
   // Q^T fragments: lane = query (l32), 8 consecutive dims per 16-wide k slice
   bf16x8 qf[8];
@@ -400,7 +383,6 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
     left -= BN;
   }
 
-  DBG_CLK_END(NW == 8)
   // ---- epilogue: normalise, transpose through LDS, store whole rows
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.f / l_tot;
@@ -487,7 +469,6 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
-  DBG_CLK_BEGIN
 
   bf16x8 qf[8];
   {
@@ -654,9 +635,6 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   };
 #pragma unroll
   for (int n = 0; n < LEAD; ++n) vpre[n] = v_frag(v_rd, n);       // iteration 0 multiplies stage 0 by P = 0
-#ifdef PIPE_STAMPS
-  unsigned stamp_acc[6] = {0, 0, 0, 0, 0, 0};
-#endif
   // One iteration.  sc*: scores of block i (in), sn*: scores of block i+1 (out),
   // pp: P^T(i-1) (in), pc: P^T(i) (out).
   auto body = [&](int i, f32x16& sc0, f32x16& sc1, f32x16& sn0, f32x16& sn1, bf16x8 (&pp)[NKS], bf16x8 (&pc)[NKS]) {
@@ -668,10 +646,6 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
     bf16x8 vf[NPV], kf[NS - NPV];
     auto v_req = [&](int n) { vf[n] = v_frag(vq, n); };
     auto k_req = [&](int n) { kf[n] = lds_frag3(KB == 64 ? kq + 32 * (n & 1) * LSTR + 16 * (n >> 1) : kq + 16 * n); };
-#ifdef PIPE_STAMPS
-    unsigned long long ts0, ts1, ts2, ts3, ts4, ts5;
-    asm volatile("s_memtime %0" : "=s"(ts0));
-#endif
     const lds_ptr vq_next = opaque(v_rd + (i & 3) * STAGE_ELEMS);     // V(i): second product of iteration i+1
 #pragma unroll
     for (int n = 0; n < LEAD; ++n) vf[n] = vpre[n];
@@ -683,12 +657,6 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
 #pragma unroll
     for (int n = 0; n < NS; ++n) {
       SLOT_FENCE();
-#ifdef PIPE_STAMPS
-      if (n == 1) asm volatile("s_memtime %0" : "=s"(ts1));
-      if (n == NS / 4) asm volatile("s_memtime %0" : "=s"(ts2));
-      if (n == NS / 2) asm volatile("s_memtime %0" : "=s"(ts3));
-      if (n == 3 * NS / 4) asm volatile("s_memtime %0" : "=s"(ts4));
-#endif
       // ---- matrix instruction of the slot
       if (n < NPV) {
         o[n & 3] = MFMA(vf[n], pp[n >> 2], o[n & 3]);
@@ -758,18 +726,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
     ps1 = pair_sum(u[LP >> 3][LP & 7], ps1);
     float ps = ps0 + ps1;
     asm volatile("" : "+v"(u[LP >> 3][LP & 7]), "+v"(ps));
-#ifdef PIPE_STAMPS
-    asm volatile("s_memtime %0" : "=s"(ts5));
-#endif
     __syncthreads();
-#ifdef PIPE_STAMPS
-    {
-      unsigned long long ts6;
-      asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts6));
-      stamp_acc[0] += (unsigned)(ts1 - ts0); stamp_acc[1] += (unsigned)(ts2 - ts1); stamp_acc[2] += (unsigned)(ts3 - ts2);
-      stamp_acc[3] += (unsigned)(ts4 - ts3); stamp_acc[4] += (unsigned)(ts5 - ts4); stamp_acc[5] += (unsigned)(ts6 - ts5);
-    }
-#endif
     // ---- reference check.  No probability exceeds its row sum, so ps <= P_MAX proves that no
     // score of the block was more than log2(P_MAX) above the reference.  Otherwise (always for
     // the first block, whose reference is -inf; afterwards only when a row maximum jumps) the
@@ -845,11 +802,6 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
     for (int n = 0; n < NPV; ++n)
       o[n & 3] = MFMA(n < LEAD ? vpre[n] : v_frag(vq, n), pa[n >> 2], o[n & 3]);
   }
-  DBG_CLK_END(true)
-#ifdef PIPE_STAMPS
-  if (blockIdx.x == 300 && lane == 0 && (wave == 0 || wave == NWV / 2 || wave == NWV - 1))
-    for (int k = 0; k < 6; ++k) g_dbg_stamps[(wave == 0 ? 0 : wave == NWV / 2 ? 1 : 2) * 6 + k] = stamp_acc[k];
-#endif
   __syncthreads();   // every wavefront is done with the ring before stage 0 is reused below
 
   // ---- epilogue: normalise, transpose through LDS, store whole rows
@@ -922,11 +874,3 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
 
 }  // namespace vorta
 
-#ifdef VORTA_DEBUG_CLOCKS
-extern "C" int vorta_debug_stamps(unsigned* out18) {
-  return hipMemcpyFromSymbol(out18, HIP_SYMBOL(vorta::g_dbg_stamps), sizeof(unsigned) * 18) == hipSuccess ? 0 : -6;
-}
-extern "C" int vorta_debug_clocks(long long* out4) {
-  return hipMemcpyFromSymbol(out4, HIP_SYMBOL(vorta::g_dbg_clk), sizeof(long long) * 16) == hipSuccess ? 0 : -6;
-}
-#endif
