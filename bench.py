@@ -33,10 +33,16 @@ ATTN_TRAFFIC_BYTES = (8640732 + 264600) * 1024
 
 def layer_flops(cfg, plan, routes):
     """QK^T and PV multiply-adds (2 FLOP each) each route has to do; returns per-route totals."""
-    d, N, L, Lt = cfg.head_dim, cfg.n_tokens, cfg.n_video, cfg.n_text
-    kw = plan.window_key_tiles * plan.tile_tokens
+    import numpy as np
+    import paper_2505_18809_amd as vorta
+    d, N, Lt = cfg.head_dim, cfg.n_tokens, cfg.n_text
+    # window heads: every query of a tile sees the keys of the tile's run list (text keys included);
+    # counted from the plan's host tables, so clipped edge tiles and truncated windows are exact
+    runs, n_runs = vorta.vorta_window_runs(plan)
+    keys = np.array([runs[t, :n_runs[t], 1].sum() for t in range(plan.n_tiles)], dtype=np.float64)
+    rows = np.diff(vorta.vorta_tile_row0(plan)).astype(np.float64)
     per_head = [4.0 * N * N * d,
-                4.0 * d * (L * (kw + Lt) + Lt * N),
+                4.0 * d * (float((rows * keys).sum()) + Lt * N),
                 4.0 * (plan.n_core + Lt) ** 2 * d]
     counts = [int((routes == r).sum()) for r in range(3)]
     return [per_head[r] * counts[r] for r in range(3)], per_head, counts

@@ -66,7 +66,8 @@ typedef struct vorta_layer_desc {
   int32_t head_dim;         /* bf16: 128; fp32: 64 or 128                                    */
   int32_t dtype;            /* VORTA_F32 | VORTA_BF16 (inputs, outputs and internal buffers) */
   int32_t layout;           /* VORTA_LAYOUT_*                                                */
-  int32_t tile[3];          /* tokens per tile (t_F, t_H, t_W); must divide the grid         */
+  int32_t tile[3];          /* tokens per tile (t_F, t_H, t_W) >= 1; where a tile does not divide
+                               the grid axis, the last tile of that axis is clipped to the grid */
   int32_t window[3];        /* window in TILES, the unit Algorithm 1 compares; >= 1          */
   int32_t center_mode;      /* VORTA_CENTER_*: how get_window_center_id treats border tiles  */
   int32_t bucket[3];        /* BCS bucket, the paper uses (2,3,2); border buckets are clipped */
@@ -79,9 +80,9 @@ typedef struct vorta_plan vorta_plan;   /* opaque */
 typedef struct vorta_plan_info {
   int64_t n_video;          /* L                                                             */
   int64_t n_tokens;         /* N = L + n_text                                                */
-  int32_t tiles[3];         /* tile grid n = grid / tile                                     */
+  int32_t tiles[3];         /* tile grid n = ceil(grid / tile)                               */
   int32_t n_tiles;
-  int32_t tile_tokens;      /* tokens per tile                                               */
+  int32_t tile_tokens;      /* tokens of a full (unclipped) tile                             */
   int32_t window_key_tiles; /* key tiles every video query sees (clamp mode; max otherwise)  */
   int32_t max_runs;         /* row stride of the window run table                            */
   int32_t n_buckets;
@@ -104,9 +105,14 @@ int vorta_plan_info_get(const vorta_plan* plan, vorta_plan_info* out);
 /* ---- host tables: deterministic integers, checkable without a GPU ----------------------- */
 
 /* Tile order (Algorithm 1's get_tile_id_3d made a storage order): token with raster index i
- * goes to position perm[i] = tile_id * tile_tokens + local_id, tile ids and local ids both
- * frame-major inside their grids.  perm: host int32[L]. */
+ * goes to position perm[i] = tile_row0[tile_id] + local_id, tile ids frame-major in the tile
+ * grid, local ids frame-major inside the tile's own (possibly clipped) extents.  When the tile
+ * divides the grid, tile_row0[t] = t * tile_tokens.  perm: host int32[L]. */
 int vorta_tile_permutation(const vorta_plan* plan, int32_t* perm);
+
+/* First tile-order row of every tile; tile t owns rows [tile_row0[t], tile_row0[t + 1]).
+ * tile_row0: host int32[n_tiles + 1] (last entry = L). */
+int vorta_tile_row0(const vorta_plan* plan, int32_t* tile_row0);
 
 /* Algorithm 1 per query tile: the key tiles with abs(centre_d - k_d) <= window_d / 2 form
  * the box [lo_d, hi_d] (inclusive) returned as boxes[tile][6] = {loF,hiF,loH,hiH,loW,hiW}.

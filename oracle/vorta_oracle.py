@@ -17,7 +17,8 @@ What each function follows:
 Readings taken where the paper is silent (kept in one place so a reader can
 check them):
   * tokens are the (F,H,W) grid flattened frame-major; 0-based indices.
-  * get_tile_id_3d = per-axis floor(coord / tile).
+  * get_tile_id_3d = per-axis floor(coord / tile); where the tile does not
+    divide an axis, the last tile of that axis is clipped to the grid.
   * get_window_center_id clamps the query tile id so the window stays inside
     the tile grid (mode "clamp", the sliding-*tile* behaviour); mode
     "identity" leaves it unchanged (windows truncated at the border).
@@ -81,10 +82,11 @@ def get_tile_id_3d(i: int, grid, tile) -> Tuple[int, int, int]:
 
 
 def tile_grid(grid, tile) -> Tuple[int, int, int]:
-    for g, t in zip(grid, tile):
-        if g % t:
-            raise ValueError(f"grid {grid} not divisible by tile {tile}")
-    return (grid[0] // tile[0], grid[1] // tile[1], grid[2] // tile[2])
+    """Tiles per axis.  Algorithm 1 assigns tile ids by integer division of the
+    token coordinate, whatever the grid: when the tile does not divide an axis
+    the last tile of that axis is simply smaller, so there are ceil(G / t) of
+    them (the same clipping as for edge buckets)."""
+    return tuple(-(-g // t) for g, t in zip(grid, tile))
 
 
 def get_window_center_id(q, n_tiles, window, mode: str = "clamp"):

@@ -20,7 +20,7 @@ VORTA_MAX_HEADS = 128
 
 SYMBOLS = [
     "vorta_strerror", "vorta_last_error", "vorta_plan_create", "vorta_plan_destroy", "vorta_plan_info_get",
-    "vorta_tile_permutation", "vorta_window_boxes", "vorta_window_runs", "vorta_bcs_slot_bases",
+    "vorta_tile_permutation", "vorta_tile_row0", "vorta_window_boxes", "vorta_window_runs", "vorta_bcs_slot_bases",
     "vorta_probe_mfma_rate", "vorta_route_partition", "vorta_router_gates", "vorta_route_select", "vorta_reorder_to_tiles", "vorta_reorder_from_tiles",
     "vorta_bcs_build_index", "vorta_bcs_pool", "vorta_attention_routed", "vorta_scatter_back",
     "vorta_workspace_bytes", "vorta_workspace_layout", "vorta_routed_attention_layer",
@@ -176,6 +176,12 @@ def vorta_tile_permutation(plan: Plan) -> np.ndarray:
     perm = np.empty(plan.n_video, dtype=np.int32)
     _check(load_library().vorta_tile_permutation(plan.handle, _i32p(perm)))
     return perm
+
+
+def vorta_tile_row0(plan: Plan) -> np.ndarray:
+    row0 = np.empty(plan.n_tiles + 1, dtype=np.int32)
+    _check(load_library().vorta_tile_row0(plan.handle, _i32p(row0)))
+    return row0
 
 
 def vorta_window_boxes(plan: Plan) -> np.ndarray:

@@ -33,6 +33,7 @@ int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io,
   a->qc = io->q_c; a->kc = io->k_c; a->vc = io->v_c; a->oc = io->o_c;
   a->qt = io->q_t; a->kt = io->k_t; a->vt = io->v_t; a->ot = io->o_t;
   a->tok_of = p->d_tok_of;
+  a->tile_row0 = p->d_tile_row0;
   a->win_gather = io->q_t == nullptr;
   a->runs = p->d_runs;
   a->n_runs = p->d_n_runs;

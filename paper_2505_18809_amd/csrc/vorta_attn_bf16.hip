@@ -155,6 +155,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   const uint16_t* V = (const uint16_t*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
   uint16_t* O = (uint16_t*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
   const unsigned row_stride = (unsigned)w.row_stride;   // rows * stride < 2^31 elements (checked on the host)
+  if (w.n_rows <= 0) return;       // q-block past the end of a clipped tile
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
@@ -465,7 +466,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   uint16_t* O = (uint16_t*)(w.seg == 0 || WIN ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
   const unsigned row_stride = (unsigned)w.row_stride;
 
-  if (w.n_rows <= 0) return;       // second half of a split item whose rows all lie in the first half
+  if (w.n_rows <= 0) return;       // no rows: second half of a split item, or a q-block past the end of a clipped tile
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;

@@ -31,6 +31,7 @@ struct AttnArgs {
   // route 1 without tile-ordered copies (qt == null): rows of the caller's tensors are gathered
   // through tok_of (tile-order index -> token index); win_heads = head id of each window slot
   const int* tok_of;                // [N]
+  const int* tile_row0;             // [n_tiles + 1]: first tile-order row of each tile (edge tiles may be clipped)
   int win_gather;
   const int* runs;                  // [n_tiles][max_runs][2]
   const int* n_runs;                // [n_tiles]
@@ -104,13 +105,14 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
     w.seg = 2;
     w.q_off = w.kv_off = w.o_off = a.win_gather ? a.win_heads[slot] * a.head_stride0 : (long)slot * a.N * D;
     w.row_stride = a.win_gather ? a.row_stride0 : D;
-    w.row0 = tile * a.tile_tokens + qb * BM;
-    w.n_rows = min(BM, a.tile_tokens - qb * BM);
+    const int first = a.tile_row0[tile];
+    w.row0 = first + qb * BM;
+    w.n_rows = min(BM, a.tile_row0[tile + 1] - first - qb * BM);   // <= 0 for a clipped tile with fewer q-blocks
     w.runs = a.runs + (long)tile * a.max_runs * 2;
     w.n_runs = a.n_runs[tile];
     w.single_len = 0;
   }
-  if (half >= 0) {          // n_rows may come out <= 0: the workgroup then has nothing to do
+  if (half >= 0) {          // n_rows may come out <= 0 here too: the workgroup then has nothing to do
     w.row0 += half * (BM / 2);
     w.n_rows = min(BM / 2, w.n_rows - half * (BM / 2));
   }

@@ -20,6 +20,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const AttnArgs a) {
   const float* K = (const float*)(w.seg == 0 ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
   const float* V = (const float*)(w.seg == 0 ? a.v0 : w.seg == 1 ? a.vc : a.vt) + w.kv_off;
   float* O = (float*)(w.seg == 0 ? a.o0 : w.seg == 1 ? a.oc : a.ot) + w.o_off;
+  if (w.n_rows <= 0) return;       // q-block past the end of a clipped tile
   const int t = threadIdx.x;
   const long my_row = w.row0 + min(t, w.n_rows - 1);
 

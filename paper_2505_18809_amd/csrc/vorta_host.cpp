@@ -102,8 +102,7 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
   const int grid[3] = {d.F, d.H, d.W};
   int64_t bucket_tokens = 1;
   for (int a = 0; a < 3; ++a) {
-    if (d.tile[a] < 1 || grid[a] % d.tile[a])
-      return fail(VORTA_ESHAPE, "tile[%d] = %d does not divide grid %d", a, d.tile[a], grid[a]);
+    if (d.tile[a] < 1) return fail(VORTA_ESHAPE, "tile[%d] = %d < 1", a, d.tile[a]);
     if (d.window[a] < 1) return fail(VORTA_ESHAPE, "window[%d] = %d < 1", a, d.window[a]);
     if (d.bucket[a] < 1) return fail(VORTA_ESHAPE, "bucket[%d] = %d < 1", a, d.bucket[a]);
     bucket_tokens *= d.bucket[a];
@@ -121,11 +120,27 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
   p->scale = d.softmax_scale > 0.f ? d.softmax_scale : (float)(1.0 / std::sqrt((double)d.head_dim));
   p->tile_tokens = d.tile[0] * d.tile[1] * d.tile[2];
   for (int a = 0; a < 3; ++a) {
-    p->nt[a] = grid[a] / d.tile[a];
+    p->nt[a] = (grid[a] + d.tile[a] - 1) / d.tile[a];   // the last tile of an axis is clipped to the grid
     p->nb[a] = (grid[a] + d.bucket[a] - 1) / d.bucket[a];
   }
   p->n_tiles = p->nt[0] * p->nt[1] * p->nt[2];
   p->n_buckets = p->nb[0] * p->nb[1] * p->nb[2];
+
+  // Tile order: tiles in raster order of their ids, the tokens of a tile in raster order of
+  // their local coordinates; tile_row0 = first row of each tile.
+  p->tile_row0.resize((size_t)p->n_tiles + 1);
+  {
+    int64_t row = 0;
+    int t = 0;
+    for (int tf = 0; tf < p->nt[0]; ++tf)
+      for (int th = 0; th < p->nt[1]; ++th)
+        for (int tw = 0; tw < p->nt[2]; ++tw) {
+          p->tile_row0[t++] = (int32_t)row;
+          row += (int64_t)std::min(d.tile[0], d.F - tf * d.tile[0]) * std::min(d.tile[1], d.H - th * d.tile[1]) *
+                 std::min(d.tile[2], d.W - tw * d.tile[2]);
+        }
+    p->tile_row0[t] = (int32_t)row;   // = L
+  }
 
   // Algorithm 1: key-tile box of every query tile.
   p->boxes.resize((size_t)p->n_tiles * 6);
@@ -160,8 +175,9 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
         };
         for (int kf = lo[0]; kf <= hi[0]; ++kf)
           for (int kh = lo[1]; kh <= hi[1]; ++kh) {
-            const int64_t first = ((int64_t)(kf * p->nt[1] + kh) * p->nt[2] + lo[2]) * p->tile_tokens;
-            push(first, (int64_t)(hi[2] - lo[2] + 1) * p->tile_tokens);
+            const int row_of_tiles = (kf * p->nt[1] + kh) * p->nt[2];
+            const int64_t first = p->tile_row0[row_of_tiles + lo[2]];
+            push(first, p->tile_row0[row_of_tiles + hi[2] + 1] - first);
           }
         if (d.n_text > 0) push(p->L, d.n_text);
       }
@@ -219,10 +235,20 @@ int vorta_tile_permutation(const vorta_plan* p, int32_t* perm) {
   for (int f = 0; f < d.F; ++f)
     for (int h = 0; h < d.H; ++h)
       for (int w = 0; w < d.W; ++w, ++i) {
-        const int tile = ((f / d.tile[0]) * p->nt[1] + h / d.tile[1]) * p->nt[2] + w / d.tile[2];
-        const int local = ((f % d.tile[0]) * d.tile[1] + h % d.tile[1]) * d.tile[2] + w % d.tile[2];
-        perm[i] = tile * p->tile_tokens + local;
+        const int tf = f / d.tile[0], th = h / d.tile[1], tw = w / d.tile[2];
+        const int tile = (tf * p->nt[1] + th) * p->nt[2] + tw;
+        const int ext_h = std::min(d.tile[1], d.H - th * d.tile[1]);   // extents of this (possibly clipped) tile
+        const int ext_w = std::min(d.tile[2], d.W - tw * d.tile[2]);
+        const int local = ((f % d.tile[0]) * ext_h + h % d.tile[1]) * ext_w + w % d.tile[2];
+        perm[i] = p->tile_row0[tile] + local;
       }
+  return VORTA_OK;
+}
+
+int vorta_tile_row0(const vorta_plan* p, int32_t* tile_row0) {
+  clear_error();
+  if (!p || !tile_row0) return fail(VORTA_EINVAL, "null plan or tile_row0");
+  std::copy(p->tile_row0.begin(), p->tile_row0.end(), tile_row0);
   return VORTA_OK;
 }
 

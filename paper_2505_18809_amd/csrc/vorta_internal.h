@@ -19,6 +19,9 @@ struct vorta_plan {
   int window_key_tiles = 0;
   int elem_bytes = 0;
   float scale = 0.f;
+  // first row of every tile in tile order, [n_tiles + 1]: a tile that the grid clips (the tile
+  // does not divide the axis) holds fewer rows than tile_tokens
+  std::vector<int32_t> tile_row0;
   std::vector<int32_t> boxes;    // [n_tiles][6]
   std::vector<int32_t> runs;     // [n_tiles][max_runs][2]
   std::vector<int32_t> n_runs;   // [n_tiles]
@@ -34,6 +37,7 @@ struct vorta_plan {
   int32_t* d_n_runs = nullptr;
   int32_t* d_slot_base = nullptr;
   int32_t* d_tok_of = nullptr;   // [N]
+  int32_t* d_tile_row0 = nullptr;   // [n_tiles + 1]
 };
 
 namespace vorta {

@@ -43,6 +43,9 @@ int ensure_device_tables(vorta_plan* p) {
     VORTA_HIP(hipMalloc(&p->d_tok_of, tok_of.size() * sizeof(int32_t)));
     VORTA_HIP(hipMemcpy(p->d_tok_of, tok_of.data(), tok_of.size() * sizeof(int32_t), hipMemcpyHostToDevice));
   }
+  VORTA_HIP(hipMalloc(&p->d_tile_row0, p->tile_row0.size() * sizeof(int32_t)));
+  VORTA_HIP(hipMemcpy(p->d_tile_row0, p->tile_row0.data(), p->tile_row0.size() * sizeof(int32_t),
+                      hipMemcpyHostToDevice));
   {
     int cus = 0;
     VORTA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
@@ -67,9 +70,6 @@ static HeadList head_list(const RouteLists& rl, int route) {
 
 struct Geo {
   int F, H, W;
-  int tF, tH, tW;
-  int nH, nW;       // tile grid along H, W
-  int tile_tokens;
   int L, N;
   int bF, bH, bW;   // bucket
   int nbH, nbW;     // bucket grid along H, W
@@ -79,9 +79,6 @@ struct Geo {
 static Geo make_geo(const vorta_plan* p) {
   Geo g;
   g.F = p->d.F; g.H = p->d.H; g.W = p->d.W;
-  g.tF = p->d.tile[0]; g.tH = p->d.tile[1]; g.tW = p->d.tile[2];
-  g.nH = p->nt[1]; g.nW = p->nt[2];
-  g.tile_tokens = p->tile_tokens;
   g.L = (int)p->L; g.N = (int)p->N;
   g.bF = p->d.bucket[0]; g.bH = p->d.bucket[1]; g.bW = p->d.bucket[2];
   g.nbH = p->nb[1]; g.nbW = p->nb[2];
@@ -89,33 +86,21 @@ static Geo make_geo(const vorta_plan* p) {
   return g;
 }
 
-// Position in tile order -> frame-major raster index (inverse of get_tile_id_3d + local id).
-__device__ __forceinline__ int tiled_to_raster(const Geo& g, int pos) {
-  const int tile = pos / g.tile_tokens, local = pos - tile * g.tile_tokens;
-  const int tiles_hw = g.nH * g.nW;
-  const int tf = tile / tiles_hw, tr = tile - tf * tiles_hw;
-  const int th = tr / g.nW, tw = tr - th * g.nW;
-  const int loc_hw = g.tH * g.tW;
-  const int lf = local / loc_hw, lr = local - lf * loc_hw;
-  const int lh = lr / g.tW, lw = lr - lh * g.tW;
-  return ((tf * g.tF + lf) * g.H + th * g.tH + lh) * g.W + tw * g.tW + lw;
-}
-
 // ------------------------------------------------------------------------------------------
 // reorder: one thread per (tile-order row, 16-byte chunk), looping over the heads of route 1
 // ------------------------------------------------------------------------------------------
 template <bool TO_TILES>
 __global__ __launch_bounds__(256) void reorder_kernel(uint4* __restrict__ user, uint4* __restrict__ tiled,
-                                                      HeadList hl, Geo g, long head_stride_c,
-                                                      long row_stride_c, int cshift) {
+                                                      const int* __restrict__ tok_of, HeadList hl, int N,
+                                                      long head_stride_c, long row_stride_c, int cshift) {
   const long gid = (long)blockIdx.x * 256 + threadIdx.x;
   const int pos = (int)(gid >> cshift);
   const int c = (int)(gid & ((1 << cshift) - 1));
-  if (pos >= g.N) return;
-  const int i = pos < g.L ? tiled_to_raster(g, pos) : pos;   // text rows keep their place
+  if (pos >= N) return;
+  const int i = tok_of[pos];   // tile-order row -> token (text rows keep their place)
   const long u0 = (long)i * row_stride_c + c;
   const long t0 = ((long)pos << cshift) + c;
-  const long tiled_head = (long)g.N << cshift;
+  const long tiled_head = (long)N << cshift;
 #pragma unroll 4
   for (int s = 0; s < hl.n; ++s) {
     const long u = u0 + hl.id[s] * head_stride_c, t = t0 + s * tiled_head;
@@ -138,14 +123,13 @@ int launch_reorder(vorta_plan* p, const RouteLists& rl, const void* user, void* 
   const long total = (long)p->N << cs;
   const unsigned blocks = (unsigned)((total + 255) / 256);
   const HeadList hl = head_list(rl, 1);
-  const Geo g = make_geo(p);
   hipStream_t st = (hipStream_t)stream;
   if (to_tiles)
-    hipLaunchKernelGGL(reorder_kernel<true>, dim3(blocks), dim3(256), 0, st, (uint4*)user, (uint4*)tiled, hl, g,
-                       ut.head_stride / epc, ut.row_stride / epc, cs);
+    hipLaunchKernelGGL(reorder_kernel<true>, dim3(blocks), dim3(256), 0, st, (uint4*)user, (uint4*)tiled,
+                       p->d_tok_of, hl, (int)p->N, ut.head_stride / epc, ut.row_stride / epc, cs);
   else
-    hipLaunchKernelGGL(reorder_kernel<false>, dim3(blocks), dim3(256), 0, st, (uint4*)user, (uint4*)tiled, hl,
-                       g, ut.head_stride / epc, ut.row_stride / epc, cs);
+    hipLaunchKernelGGL(reorder_kernel<false>, dim3(blocks), dim3(256), 0, st, (uint4*)user, (uint4*)tiled,
+                       p->d_tok_of, hl, (int)p->N, ut.head_stride / epc, ut.row_stride / epc, cs);
   return launch_status("reorder_kernel");
 }
 
@@ -506,6 +490,7 @@ extern "C" int vorta_plan_destroy(vorta_plan* p) {
     (void)hipFree(p->d_n_runs);
     (void)hipFree(p->d_slot_base);
     (void)hipFree(p->d_tok_of);
+    (void)hipFree(p->d_tile_row0);
   }
   delete p;
   return VORTA_OK;

@@ -62,6 +62,11 @@ CONFIGS = (
 EXTRA_CONFIGS = (
     LayerConfig("paper720p", (30, 45, 80), 24, 128, "bf16", (6, 9, 8), (3, 3, 3), seed=5,
                 n_text=256, route_fractions=(0.0, 0.5, 0.5)),
+    # the same appendix's second model: Wan 2.1 at 720p / 77 frames = 20x45x80 latents, 40 heads,
+    # no text tokens in self-attention; 6 frames per tile do not divide 20, so the last tile
+    # layer along F is clipped to 2 frames
+    LayerConfig("paper_wan720p", (20, 45, 80), 40, 128, "bf16", (6, 9, 8), (3, 3, 3), seed=6,
+                route_fractions=(0.0, 0.5, 0.5)),
 )
 
 

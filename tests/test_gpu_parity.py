@@ -190,6 +190,42 @@ def test_text_rows_spanning_several_query_blocks(n_text, layout):
     check_layer(cfg, cfg.fixed_routes, layout=layout)
 
 
+@pytest.mark.parametrize("grid,tile,dtype", [((5, 7, 6), (2, 3, 4), "bf16"), ((5, 7, 6), (2, 3, 4), "fp32"),
+                                             ((7, 10, 13), (3, 4, 5), "bf16"), ((9, 11, 14), (4, 6, 8), "bf16"),
+                                             ((3, 5, 5), (4, 2, 6), "bf16"), ((10, 12, 9), (6, 9, 8), "bf16")])
+@pytest.mark.parametrize("layout", [1, 0])
+def test_layers_whose_tiles_do_not_divide_the_grid(grid, tile, dtype, layout):
+    """Edge tiles clipped to the grid: ragged tile sizes in the tile order, in the run lists and
+    in the work items (a clipped tile can have fewer query blocks than a full one).  Tiles below
+    and above 128 tokens, text rows, every route, both centre rules."""
+    d = 64 if dtype == "fp32" else 128
+    cfg = small_cfg(f"clip{grid}", grid, 5, dtype, tile, (3, 3, 3), [1, 0, 1, 2, 1], d=d, n_text=9, seed=61)
+    check_layer(cfg, cfg.fixed_routes, layout=layout)
+    check_layer(cfg, cfg.fixed_routes, layout=layout, center_mode=1)
+    # the staged path over tile-ordered copies (reorder passes, plain window kernel)
+    if layout == 1 and dtype == "bf16":
+        routes = np.array(cfg.fixed_routes, dtype=np.uint8)
+        q, k, v = make_qkv(cfg, DEV)
+        plan = vorta.plan_for(cfg)
+        q_t, k_t, v_t = (vorta.vorta_reorder_to_tiles(plan, t, routes) for t in (q, k, v))
+        perm = torch.as_tensor(vorta.vorta_tile_permutation(plan), device=DEV, dtype=torch.long)
+        for slot, h in enumerate(np.nonzero(routes == 1)[0]):
+            want = torch.empty_like(q[h])
+            want[perm] = q[h][: cfg.n_video]
+            want[cfg.n_video:] = q[h][cfg.n_video:]
+            assert torch.equal(q_t[slot], want)
+        o_t, staged = torch.empty_like(q_t), torch.zeros_like(q)
+        only_win = np.where(routes == 1, 1, 0).astype(np.uint8)      # window heads; the rest as dense heads
+        vorta.vorta_attention_routed(plan, only_win, q=q, k=k, v=v, out=staged, q_t=q_t, k_t=k_t, v_t=v_t, o_t=o_t)
+        vorta.vorta_scatter_back(plan, only_win, o_t, None, None, staged)
+        torch.cuda.synchronize()
+        spec = spec_of(cfg)
+        for h in np.nonzero(routes == 1)[0]:
+            want = vo.head_attention(1, f64(q[h]), f64(k[h]), f64(v[h]), spec, None)
+            err = np.abs(f64(staged[h]) - want).max()
+            assert err <= TOL["bf16"], f"staged window head {h}: max-abs {err:.3e}"
+
+
 def test_window_identity_centres_and_wide_windows():
     cfg = small_cfg("ident", (4, 8, 8), 2, "bf16", (2, 2, 2), (1, 3, 5), [1, 1])
     check_layer(cfg, cfg.fixed_routes, center_mode=1)
@@ -353,20 +389,21 @@ def sampled_rows(cfg, plan, head, rng):
     and of an interior tile, the last rows, and all text rows."""
     L = cfg.n_video
     perm = vorta.vorta_tile_permutation(plan)
-    tt = plan.tile_tokens
-    corner = np.nonzero(perm // tt == 0)[0]
-    mid = np.nonzero(perm // tt == plan.n_tiles // 2 + plan.tiles[2] // 2)[0]
+    tile_of = np.searchsorted(vorta.vorta_tile_row0(plan), perm, side="right") - 1
+    corner = np.nonzero(tile_of == 0)[0]
+    mid = np.nonzero(tile_of == plan.n_tiles // 2 + plan.tiles[2] // 2)[0]
+    last = np.nonzero(tile_of == plan.n_tiles - 1)[0]      # clipped on every axis the tile does not divide
     # 512 random rows, every row of a corner tile and of a tile in the middle of the grid, the
     # last video rows (ragged tail of the last query block) and every text row
     # (tiles of more than 128 tokens: every other / third ... row, so that they cost no more)
     step = max(1, len(corner) // 128)
     n_random = 512 if plan.tile_tokens <= 128 else 192
-    rows = np.concatenate([rng.choice(L, n_random, replace=False), corner[::step], mid[::step], np.arange(L - 3, L),
-                           L + np.arange(cfg.n_text)])
+    rows = np.concatenate([rng.choice(L, n_random, replace=False), corner[::step], mid[::step], last[::step],
+                           np.arange(L - 3, L), L + np.arange(cfg.n_text)])
     return np.unique(rows)
 
 
-@pytest.mark.parametrize("name", ["wan480p", "wan720p", "hunyuan720p", "paper720p"])
+@pytest.mark.parametrize("name", ["wan480p", "wan720p", "hunyuan720p", "paper720p", "paper_wan720p"])
 def test_full_size_layer_on_sampled_rows(name):
     cfg = get_config(name)
     routes = make_routes(cfg).numpy()

@@ -41,27 +41,34 @@ def test_plan_geometry(cfg):
     assert plan.window_key_tiles == int(np.prod([min(3, n) for n in plan.tiles]))
 
 
-@pytest.mark.parametrize("grid,tile", [((4, 8, 8), (2, 4, 4)), ((3, 4, 6), (1, 2, 3)), ((12, 16, 16), (4, 4, 4))])
+@pytest.mark.parametrize("grid,tile", [((4, 8, 8), (2, 4, 4)), ((3, 4, 6), (1, 2, 3)), ((12, 16, 16), (4, 4, 4)),
+                                       ((5, 7, 6), (2, 3, 4)), ((3, 5, 5), (4, 2, 6)), ((20, 9, 10), (6, 9, 8))])
 def test_tile_permutation_matches_get_tile_id_3d(grid, tile):
+    """Also on grids the tile does not divide (clipped edge tiles)."""
     plan = vorta.vorta_plan_create(grid, 1, 128, "bf16", tile, (3, 3, 3))
     perm = vorta.vorta_tile_permutation(plan)
+    row0 = vorta.vorta_tile_row0(plan)
     L = int(np.prod(grid))
     assert sorted(perm) == list(range(L))
     n = vo.tile_grid(grid, tile)
-    tt = int(np.prod(tile))
+    assert plan.tiles == n and len(row0) == plan.n_tiles + 1 and row0[0] == 0 and row0[-1] == L
+    tile_of_row = np.searchsorted(row0, np.arange(L), side="right") - 1
     for i in range(L):
         tid = vo.get_tile_id_3d(i, grid, tile)
-        assert perm[i] // tt == np.ravel_multi_index(tid, n)
+        assert tile_of_row[perm[i]] == np.ravel_multi_index(tid, n)
     # inside a tile, positions follow raster order of the tokens
     for t in range(plan.n_tiles):
-        members = np.nonzero(perm // tt == t)[0]
-        assert (np.diff(perm[members]) == 1).all() and perm[members[0]] == t * tt
+        members = np.nonzero(tile_of_row[perm] == t)[0]
+        assert (np.diff(perm[members]) == 1).all() and perm[members[0]] == row0[t]
+    if all(g % t == 0 for g, t in zip(grid, tile)):
+        assert (row0 == np.arange(plan.n_tiles + 1) * int(np.prod(tile))).all()
 
 
 @pytest.mark.parametrize("mode", ["clamp", "identity"])
 @pytest.mark.parametrize("window", [(1, 1, 1), (3, 3, 3), (1, 3, 5), (5, 2, 3)])
-def test_window_boxes_and_runs_expand_to_algorithm_1_mask(window, mode):
-    grid, tile, n_text = (4, 6, 6), (2, 2, 3), 5
+@pytest.mark.parametrize("grid,tile", [((4, 6, 6), (2, 2, 3)), ((5, 7, 6), (2, 3, 4))], ids=["divisible", "clipped"])
+def test_window_boxes_and_runs_expand_to_algorithm_1_mask(window, mode, grid, tile):
+    n_text = 5
     plan = vorta.vorta_plan_create(grid, 1, 128, "bf16", tile, window, n_text=n_text,
                                    center_mode={"clamp": 0, "identity": 1}[mode])
     M = vo.sta_mask_dense(grid, tile, window, mode)
@@ -154,7 +161,8 @@ def test_router_gates_are_softmax_of_the_projection():
 def test_bad_descriptions_are_rejected():
     ok = dict(grid=(4, 8, 8), heads=2, head_dim=128, dtype="bf16", tile=(2, 4, 4), window=(3, 3, 3))
     vorta.vorta_plan_create(**ok)
-    for bad, code in ((dict(tile=(3, 4, 4)), -2), (dict(window=(0, 1, 1)), -2), (dict(head_dim=96), -2),
+    vorta.vorta_plan_create(**{**ok, "tile": (3, 4, 4)})      # a tile that does not divide the grid is clipped
+    for bad, code in ((dict(tile=(0, 4, 4)), -2), (dict(window=(0, 1, 1)), -2), (dict(head_dim=96), -2),
                       (dict(heads=0), -2), (dict(heads=129), -2), (dict(dtype=7), -3), (dict(layout=5), -1),
                       (dict(bucket=(5, 5, 5)), -2), (dict(keep_num=3, keep_den=2), -2),
                       (dict(keep_num=0), -2), (dict(grid=(0, 8, 8)), -2)):

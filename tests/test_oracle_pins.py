@@ -141,6 +141,40 @@ def test_mask_row_form_equals_double_loop_and_invariants(window):
     assert M[np.arange(L), np.arange(L)].all()
 
 
+@pytest.mark.parametrize("window", [(1, 1, 1), (3, 3, 3), (1, 3, 5)])
+def test_mask_on_grids_the_tile_does_not_divide(window):
+    """Edge tiles are clipped: Algorithm 1's tile id is the integer division of the coordinate,
+    so the last tile of an axis just has fewer tokens.  Row form against the double loop, and
+    the key count of every row against a count written out per axis: the tiles [lo, hi] of the
+    (clamped) window cover coordinates [lo t, min(G, (hi + 1) t))."""
+    grid, tile = (5, 7, 6), (2, 3, 4)
+    n = vo.tile_grid(grid, tile)
+    assert n == (3, 3, 2)
+    M = vo.sta_mask_dense(grid, tile, window)
+    L = M.shape[0]
+    for i in range(L):
+        assert (vo.sta_mask_row(i, grid, tile, window) == M[i]).all()
+        q = vo.get_tile_id_3d(i, grid, tile)
+        count = 1
+        for a in range(3):
+            half = window[a] // 2
+            c = min(max(q[a], half), max(n[a] - 1 - half, half))
+            lo, hi = max(c - half, 0), min(c + half, n[a] - 1)
+            count *= min(grid[a], (hi + 1) * tile[a]) - lo * tile[a]
+        assert M[i].sum() == count
+    assert M[np.arange(L), np.arange(L)].all()
+    # still block-wise dense over (query tile) x (key tile) blocks, ragged ones included
+    tid = np.array([np.ravel_multi_index(vo.get_tile_id_3d(i, grid, tile), n) for i in range(L)])
+    sizes = np.bincount(tid)
+    for t_id, size in enumerate(sizes):                 # a tile holds the product of its clipped extents
+        idx = np.unravel_index(t_id, n)
+        assert size == np.prod([min(tile[a], grid[a] - idx[a] * tile[a]) for a in range(3)])
+    for a in range(len(sizes)):
+        for b in range(len(sizes)):
+            blk = M[np.ix_(tid == a, tid == b)]
+            assert blk.all() or not blk.any()
+
+
 def test_mask_covers_everything_when_window_spans_grid():
     grid, tile = (4, 6, 6), (2, 2, 3)
     n = vo.tile_grid(grid, tile)
