@@ -92,6 +92,35 @@ def test_window_boxes_and_runs_expand_to_algorithm_1_mask(window, mode, grid, ti
         assert (runs[qt, :n_runs[qt], 1] > 0).all()
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_seeded_random_geometries_expand_to_algorithm_1_mask(seed):
+    """Random small grids, tiles (dividing the grid or not), windows and centre rules: the run
+    table of every query tile, mapped back through the tile permutation, is exactly the row of
+    Algorithm 1's mask; runs are disjoint, non-empty and ascending."""
+    rng = np.random.default_rng(4000 + seed)
+    grid = tuple(int(x) for x in rng.integers(1, 8, 3))
+    tile = tuple(int(x) for x in rng.integers(1, 5, 3))
+    window = tuple(int(x) for x in rng.choice([1, 2, 3, 5, 7], 3))
+    mode = ["clamp", "identity"][seed % 2]
+    n_text = int(rng.choice([0, 3]))
+    plan = vorta.vorta_plan_create(grid, 1, 128, "bf16", tile, window, n_text=n_text, center_mode=seed % 2)
+    L = plan.n_video
+    inv = np.argsort(vorta.vorta_tile_permutation(plan))
+    row0 = vorta.vorta_tile_row0(plan)
+    runs, n_runs = vorta.vorta_window_runs(plan)
+    n = vo.tile_grid(grid, tile)
+    assert plan.tiles == n
+    for i in range(L):
+        qt = int(np.ravel_multi_index(vo.get_tile_id_3d(i, grid, tile), n))
+        r = runs[qt, :n_runs[qt]]
+        assert (r[:, 1] > 0).all() and (r[1:, 0] > r[:-1, 0] + r[:-1, 1] - 1).all()     # ascending, disjoint
+        rows = np.concatenate([np.arange(s0, s0 + c) for s0, c in r])
+        want = np.nonzero(vo.sta_mask_row(i, grid, tile, window, mode))[0]
+        assert (np.sort(inv[rows[rows < L]]) == want).all(), (grid, tile, window, mode, i)
+        assert sorted(rows[rows >= L]) == list(range(L, L + n_text))
+        assert row0[qt] <= np.nonzero(inv == i)[0][0] < row0[qt + 1]
+
+
 def test_window_covering_the_grid_is_one_run():
     cfg = get_config("tiny")
     plan = vorta.plan_for(cfg)
