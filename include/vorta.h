@@ -97,7 +97,10 @@ const char* vorta_last_error(void);     /* thread-local, valid until the thread'
 /* ---- plan: host-side geometry of one layer ---------------------------------------------- */
 
 /* Validates desc, builds the host index tables.  No HIP call.  *out is owned by the caller
- * and released with vorta_plan_destroy (which also frees the plan's device tables). */
+ * and released with vorta_plan_destroy (which also frees the plan's device tables).
+ * Size limit: (F*H*W + n_text) * row stride (head_dim, or heads * head_dim in the NHD layout)
+ * must not exceed 2^31 elements -- rows are addressed with 32-bit element offsets -- else
+ * VORTA_ESHAPE. */
 int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out);
 int vorta_plan_destroy(vorta_plan* plan);
 int vorta_plan_info_get(const vorta_plan* plan, vorta_plan_info* out);

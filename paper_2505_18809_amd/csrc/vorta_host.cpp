@@ -111,6 +111,14 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
   if (d.keep_num < 1 || d.keep_den < d.keep_num)
     return fail(VORTA_ESHAPE, "core-set ratio %d/%d outside (0, 1]", d.keep_num, d.keep_den);
 
+  {
+    // the kernels address rows of a head with 32-bit element offsets (row index times row stride)
+    const int64_t n_tokens = (int64_t)d.F * d.H * d.W + d.n_text;
+    const int64_t row_stride = d.layout == VORTA_LAYOUT_NHD ? (int64_t)d.heads * d.head_dim : d.head_dim;
+    if (n_tokens * row_stride > 0x7fffffffLL)
+      return fail(VORTA_ESHAPE, "%lld tokens x row stride %lld elements exceed 2^31 elements per tensor",
+                  (long long)n_tokens, (long long)row_stride);
+  }
   vorta_plan* p = new (std::nothrow) vorta_plan();
   if (!p) return fail(VORTA_EINVAL, "out of host memory");
   p->d = d;

@@ -194,7 +194,8 @@ def test_bad_descriptions_are_rejected():
     for bad, code in ((dict(tile=(0, 4, 4)), -2), (dict(window=(0, 1, 1)), -2), (dict(head_dim=96), -2),
                       (dict(heads=0), -2), (dict(heads=129), -2), (dict(dtype=7), -3), (dict(layout=5), -1),
                       (dict(bucket=(5, 5, 5)), -2), (dict(keep_num=3, keep_den=2), -2),
-                      (dict(keep_num=0), -2), (dict(grid=(0, 8, 8)), -2)):
+                      (dict(keep_num=0), -2), (dict(grid=(0, 8, 8)), -2),
+                      (dict(grid=(512, 256, 256), heads=64, layout=0), -2)):     # 2^25 rows x 8192 elements
         with pytest.raises(vorta.VortaError) as e:
             vorta.vorta_plan_create(**{**ok, **bad})
         assert e.value.code == code, bad
