@@ -238,7 +238,7 @@ def main():
             vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
         e1.record()
         torch.cuda.synchronize()
-        dom = {"kernel": "attn_bf16_pipe_kernel", "ms": e0.elapsed_time(e1) / args.steps,
+        dom = {"kernel": "attn_bf16_pipe_kernel<false, 8>", "ms": e0.elapsed_time(e1) / args.steps,
                "flops": per_route[0] + per_route[2]}
         del sq, sk, sv, so, sws
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
