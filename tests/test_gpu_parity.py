@@ -226,6 +226,16 @@ def test_layers_whose_tiles_do_not_divide_the_grid(grid, tile, dtype, layout):
             assert err <= TOL["bf16"], f"staged window head {h}: max-abs {err:.3e}"
 
 
+@pytest.mark.parametrize("layout", [1, 0])
+def test_maximum_head_count(layout):
+    """128 heads (the most a plan takes), routes cycling 0, 1, 2: the per-route head lists fill up
+    and every head must still read and write its own rows."""
+    heads = 128
+    routes = [h % 3 for h in range(heads)]
+    cfg = small_cfg("heads128", (2, 4, 6), heads, "bf16", (1, 2, 3), (3, 3, 3), routes, n_text=3, seed=77)
+    check_layer(cfg, routes, layout=layout)
+
+
 def test_window_identity_centres_and_wide_windows():
     cfg = small_cfg("ident", (4, 8, 8), 2, "bf16", (2, 2, 2), (1, 3, 5), [1, 1])
     check_layer(cfg, cfg.fixed_routes, center_mode=1)
