@@ -209,12 +209,12 @@ __device__ __forceinline__ int bucket_token(const Geo& g, const Bucket& k, int j
   return ((k.f0 + a) * g.H + k.h0 + b) * g.W + k.w0 + c;
 }
 
-// 16-byte chunk of a row widened to fp64 (8 bf16 or 4 fp32 elements)
+// 16-byte chunk of a row (8 bf16 or 4 fp32 elements): raw load, and widening to fp64
 template <typename T> struct Chunk;
 template <> struct Chunk<uint16_t> {
   static constexpr int N = 8;
-  __device__ static void load(const uint16_t* p, double* x) {
-    const uint4 u = *(const uint4*)p;
+  __device__ static uint4 raw(const uint16_t* p) { return *(const uint4*)p; }
+  __device__ static void widen(const uint4& u, double* x) {
     const unsigned w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -222,13 +222,15 @@ template <> struct Chunk<uint16_t> {
       x[2 * i + 1] = (double)__uint_as_float(w[i] & 0xffff0000u);
     }
   }
+  __device__ static void load(const uint16_t* p, double* x) { widen(raw(p), x); }
 };
 template <> struct Chunk<float> {
   static constexpr int N = 4;
-  __device__ static void load(const float* p, double* x) {
-    const float4 u = *(const float4*)p;
-    x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w;
+  __device__ static uint4 raw(const float* p) { return *(const uint4*)p; }
+  __device__ static void widen(const uint4& u, double* x) {
+    x[0] = __uint_as_float(u.x); x[1] = __uint_as_float(u.y); x[2] = __uint_as_float(u.z); x[3] = __uint_as_float(u.w);
   }
+  __device__ static void load(const float* p, double* x) { widen(raw(p), x); }
 };
 
 // sum over the 4 lanes of a quad (lanes 4k .. 4k+3)
@@ -241,7 +243,9 @@ __device__ __forceinline__ double quad_sum(double v) {
 // One wavefront per (bucket, head).  Four lanes share a token: lane 4t + q holds quarter q of
 // token t's feature row (16-byte loads, all rows of a pass in flight at once), so a pass of
 // the wavefront covers 16 tokens; partial dot products and norms are fp64 and are summed
-// over the quad.  Then lane j ranks token j.
+// over the quad.  Then lane j ranks token j.  The products are formed inside fused
+// multiply-adds: a product of two bf16 (or fp32) values is exact in fp64, so fusing changes
+// no bit and halves the fp64 instruction count; everything after the sums stays unfused.
 template <typename T, int D>   // D = head_dim
 __global__ __launch_bounds__(256) void bcs_index_kernel(const T* __restrict__ feat, HeadList hl, Geo g,
                                                         int n_buckets, const int* __restrict__ slot_base,
@@ -258,29 +262,37 @@ __global__ __launch_bounds__(256) void bcs_index_kernel(const T* __restrict__ fe
   const int quarter = lane & 3, tl = lane >> 2;
   const T* base = feat + hl.id[s] * head_stride + quarter * EP;
 
-  double xc[EP], nc = 0.0;
+  // The centre row and the rows of the first pass are requested together; rows stay in their
+  // 16-byte form and are widened chunk by chunk as they are used, so a bucket of up to 16
+  // tokens costs one memory round trip.
+  uint4 craw[CH];
   {
     const T* row = base + (long)bucket_token(g, k, k.centre) * row_stride;
 #pragma unroll
-    for (int ch = 0; ch < CH; ++ch) Chunk<T>::load(row + ch * Chunk<T>::N, xc + ch * Chunk<T>::N);
-#pragma unroll
-    for (int e = 0; e < EP; ++e) nc += xc[e] * xc[e];
+    for (int ch = 0; ch < CH; ++ch) craw[ch] = Chunk<T>::raw(row + ch * Chunk<T>::N);
   }
-  nc = quad_sum(nc);
-
-  double my_sim = 0.0;
+  double nc = 0.0, my_sim = 0.0;
   for (int pass = 0; pass * 16 < k.size; ++pass) {
     const int j = pass * 16 + tl;
     const bool valid = j < k.size && j != k.centre;
     const T* row = base + (long)bucket_token(g, k, valid ? j : k.centre) * row_stride;
-    double x[EP], dot = 0.0, nj = 0.0;
+    uint4 xraw[CH];
 #pragma unroll
-    for (int ch = 0; ch < CH; ++ch) Chunk<T>::load(row + ch * Chunk<T>::N, x + ch * Chunk<T>::N);
+    for (int ch = 0; ch < CH; ++ch) xraw[ch] = Chunk<T>::raw(row + ch * Chunk<T>::N);
+    double dot = 0.0, nj = 0.0, ncp = 0.0;
 #pragma unroll
-    for (int e = 0; e < EP; ++e) {
-      dot += xc[e] * x[e];
-      nj += x[e] * x[e];
+    for (int ch = 0; ch < CH; ++ch) {
+      double c[Chunk<T>::N], x[Chunk<T>::N];
+      Chunk<T>::widen(craw[ch], c);
+      Chunk<T>::widen(xraw[ch], x);
+#pragma unroll
+      for (int e = 0; e < Chunk<T>::N; ++e) {
+        ncp = __builtin_fma(c[e], c[e], ncp);
+        dot = __builtin_fma(c[e], x[e], dot);
+        nj = __builtin_fma(x[e], x[e], nj);
+      }
     }
+    if (pass == 0) nc = quad_sum(ncp);
     dot = quad_sum(dot);
     nj = quad_sum(nj);
     double sim = 0.0;
