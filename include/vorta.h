@@ -23,7 +23,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Device
  *     calls only enqueue work; they do not synchronise.  Exception: the first
  *     device call on a plan uploads the plan's small index tables with a
- *     blocking hipMalloc + hipMemcpy (a few hundred KB, once per plan).
+ *     blocking hipMalloc + hipMemcpy (a few hundred KB, once per plan) on the
+ *     device that is current then; the plan belongs to that device from then on
+ *     (a device call with another device current returns VORTA_EINVAL).
  *   - Return value: VORTA_OK or a negative error code; vorta_last_error() has
  *     a thread-local message.  Nothing is printed, thrown or aborted.  Invalid
  *     arguments are rejected before any kernel is launched.

@@ -23,33 +23,53 @@ static int launch_status(const char* what) {
   return VORTA_OK;
 }
 
+// Uploads one host table; the device pointer is registered in *slot before the copy so that a
+// failure anywhere leaves it for release_device_tables.
+template <typename T>
+static int upload_table(const std::vector<T>& host, T** slot) {
+  VORTA_HIP(hipMalloc(slot, host.size() * sizeof(T)));
+  VORTA_HIP(hipMemcpy(*slot, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
+  return VORTA_OK;
+}
+
+static void release_device_tables(vorta_plan* p) {
+  int32_t** tables[] = {&p->d_runs, &p->d_n_runs, &p->d_slot_base, &p->d_tok_of, &p->d_tile_row0};
+  for (int32_t** t : tables) {
+    if (*t) (void)hipFree(*t);
+    *t = nullptr;
+  }
+}
+
+static int upload_device_tables(vorta_plan* p, int dev) {
+  if (int rc = upload_table(p->runs, &p->d_runs)) return rc;
+  if (int rc = upload_table(p->n_runs, &p->d_n_runs)) return rc;
+  if (int rc = upload_table(p->slot_base, &p->d_slot_base)) return rc;
+  if (int rc = upload_table(p->tile_row0, &p->d_tile_row0)) return rc;
+  // tile-order row -> token (the inverse tile permutation; text rows keep their place)
+  std::vector<int32_t> perm((size_t)p->L), tok_of((size_t)p->N);
+  if (int rc = vorta_tile_permutation(p, perm.data())) return rc;
+  for (int64_t i = 0; i < p->L; ++i) tok_of[perm[i]] = (int32_t)i;
+  for (int64_t i = p->L; i < p->N; ++i) tok_of[i] = (int32_t)i;
+  if (int rc = upload_table(tok_of, &p->d_tok_of)) return rc;
+  int cus = 0;
+  VORTA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  if (cus > 0) p->n_cus = cus;
+  return VORTA_OK;
+}
+
 int ensure_device_tables(vorta_plan* p) {
   std::lock_guard<std::mutex> lock(p->mu);
-  if (p->on_device) return VORTA_OK;
   int dev = -1;
   VORTA_HIP(hipGetDevice(&dev));
-  VORTA_HIP(hipMalloc(&p->d_runs, p->runs.size() * sizeof(int32_t)));
-  VORTA_HIP(hipMalloc(&p->d_n_runs, p->n_runs.size() * sizeof(int32_t)));
-  VORTA_HIP(hipMalloc(&p->d_slot_base, p->slot_base.size() * sizeof(int32_t)));
-  VORTA_HIP(hipMemcpy(p->d_runs, p->runs.data(), p->runs.size() * sizeof(int32_t), hipMemcpyHostToDevice));
-  VORTA_HIP(hipMemcpy(p->d_n_runs, p->n_runs.data(), p->n_runs.size() * sizeof(int32_t), hipMemcpyHostToDevice));
-  VORTA_HIP(hipMemcpy(p->d_slot_base, p->slot_base.data(), p->slot_base.size() * sizeof(int32_t),
-                      hipMemcpyHostToDevice));
-  {
-    std::vector<int32_t> perm((size_t)p->L), tok_of((size_t)p->N);
-    if (int rc = vorta_tile_permutation(p, perm.data())) return rc;
-    for (int64_t i = 0; i < p->L; ++i) tok_of[perm[i]] = (int32_t)i;
-    for (int64_t i = p->L; i < p->N; ++i) tok_of[i] = (int32_t)i;
-    VORTA_HIP(hipMalloc(&p->d_tok_of, tok_of.size() * sizeof(int32_t)));
-    VORTA_HIP(hipMemcpy(p->d_tok_of, tok_of.data(), tok_of.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+  if (p->on_device) {
+    // the tables live on the device that was current at the plan's first device call
+    if (dev != p->device)
+      return fail(VORTA_EINVAL, "plan belongs to device %d, current device is %d: one plan per device", p->device, dev);
+    return VORTA_OK;
   }
-  VORTA_HIP(hipMalloc(&p->d_tile_row0, p->tile_row0.size() * sizeof(int32_t)));
-  VORTA_HIP(hipMemcpy(p->d_tile_row0, p->tile_row0.data(), p->tile_row0.size() * sizeof(int32_t),
-                      hipMemcpyHostToDevice));
-  {
-    int cus = 0;
-    VORTA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    if (cus > 0) p->n_cus = cus;
+  if (int rc = upload_device_tables(p, dev)) {
+    release_device_tables(p);      // nothing half-built is kept; the next call starts over
+    return rc;
   }
   p->device = dev;
   p->on_device = true;
@@ -497,13 +517,7 @@ int launch_blend3(vorta_plan* p, const void* o0, const void* o1, const void* o2,
 extern "C" int vorta_plan_destroy(vorta_plan* p) {
   vorta::clear_error();
   if (!p) return VORTA_OK;
-  if (p->on_device) {
-    (void)hipFree(p->d_runs);
-    (void)hipFree(p->d_n_runs);
-    (void)hipFree(p->d_slot_base);
-    (void)hipFree(p->d_tok_of);
-    (void)hipFree(p->d_tile_row0);
-  }
+  if (p->on_device) vorta::release_device_tables(p);
   delete p;
   return VORTA_OK;
 }
