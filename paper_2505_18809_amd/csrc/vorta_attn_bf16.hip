@@ -39,9 +39,9 @@ constexpr int BN = 64;          // keys per LDS block
 // 272 B, the ds_read_b64_tr_b16 pattern (4 rows x 32 B per 16 lanes) at 288 B.
 constexpr int LSTR = 136;       // K block and output staging
 constexpr int VSTR = 144;       // V block
-constexpr int KTILE = BN * LSTR;
-constexpr int STAGE_ELEMS = BN * (LSTR + VSTR);   // one K block + one V block
-constexpr int LDS_BYTES = 2 * STAGE_ELEMS * 2;
+constexpr int KTILE64 = BN * LSTR;
+constexpr int STAGE64_ELEMS = BN * (LSTR + VSTR);   // one K block + one V block
+constexpr int LDS_BYTES = 2 * STAGE64_ELEMS * 2;
 constexpr float P_MAX = 256.f;  // largest probability (relative to the row reference) the softmax fast path accepts
 }  // namespace
 
@@ -211,8 +211,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   }
 #define STAGE(buf_)                                                       \
   {                                                                       \
-    uint16_t* kb_ = smem + (buf_)*STAGE_ELEMS + ld_row * LSTR + ld_col;   \
-    uint16_t* vb_ = smem + (buf_)*STAGE_ELEMS + KTILE + ld_row * VSTR + ld_col; \
+    uint16_t* kb_ = smem + (buf_)*STAGE64_ELEMS + ld_row * LSTR + ld_col;   \
+    uint16_t* vb_ = smem + (buf_)*STAGE64_ELEMS + KTILE64 + ld_row * VSTR + ld_col; \
     *(uint4*)(kb_) = kr0;                                                 \
     *(uint4*)(kb_ + STG_ROWS * LSTR) = kr1;                               \
     *(uint4*)(vb_) = vr0;                                                 \
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   // per-lane LDS read offsets
   const uint16_t* k_rd = smem + l32 * LSTR + 8 * g;
   const int t16 = lane & 15, blk = lane >> 4;
-  const uint16_t* v_rd = smem + KTILE + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3);
+  const uint16_t* v_rd = smem + KTILE64 + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3);
 
   for (int it = 0; it < n_blocks; ++it) {
     if (it + 1 < n_blocks) { STAGE((it + 1) & 1) }        // rows requested an iteration ago
@@ -274,8 +274,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
     }
 
     const int n_valid = min(BN, left);
-    const uint16_t* kp = k_rd + (it & 1) * STAGE_ELEMS;
-    const uint16_t* vp = v_rd + (it & 1) * STAGE_ELEMS;
+    const uint16_t* kp = k_rd + (it & 1) * STAGE64_ELEMS;
+    const uint16_t* vp = v_rd + (it & 1) * STAGE64_ELEMS;
 
     // ---- S^T = K Q^T for keys [0,32) and [32,64) of the block
     f32x16 s0, s1;
@@ -428,8 +428,8 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 // ------------------------------------------------------------------------------------------
 namespace {
 constexpr int PIPE_BUFS = 4;
-constexpr int PIPE_LDS_BYTES = PIPE_BUFS * STAGE_ELEMS * 2;       // 8 wavefronts, 64-key stages
-constexpr int PIPE4_LDS_BYTES = PIPE_BUFS * (STAGE_ELEMS / 2) * 2;   // 4 wavefronts, 32-key stages
+constexpr int PIPE_LDS_BYTES = PIPE_BUFS * STAGE64_ELEMS * 2;       // 8 wavefronts, 64-key stages
+constexpr int PIPE4_LDS_BYTES = PIPE_BUFS * (STAGE64_ELEMS / 2) * 2;   // 4 wavefronts, 32-key stages
 constexpr int LEAD = 2;                  // slots between a fragment request and its use (2..6 measured alike; 2 needs the fewest registers)
 }  // namespace
 

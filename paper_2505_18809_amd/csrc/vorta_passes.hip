@@ -372,8 +372,8 @@ int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const void* feat, int3
 template <typename T, int D>
 __global__ __launch_bounds__(256) void bcs_pool_kernel(const T* __restrict__ src, HeadList hl, Geo g,
                                                        int n_buckets, long head_stride, long row_stride,
-                                                       int Lc, int n_core_rows,
-                                                       const int* __restrict__ assign, T* __restrict__ dst) {
+                                                       int n_core_rows, const int* __restrict__ assign,
+                                                       T* __restrict__ dst) {
   constexpr int CN = Chunk<T>::N;           // elements per chunk
   constexpr int CPR = D / CN;               // chunks per row: 16 or 32
   constexpr int G = 64 / CPR;               // token groups per pass
@@ -452,13 +452,13 @@ int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const 
   hipStream_t st = (hipStream_t)stream;
   if (p->d.dtype == VORTA_BF16)
     hipLaunchKernelGGL((bcs_pool_kernel<uint16_t, 128>), grid, dim3(256), 0, st, (const uint16_t*)src, hl, g,
-                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, assign, (uint16_t*)dst);
+                       p->n_buckets, ut.head_stride, ut.row_stride, rows, assign, (uint16_t*)dst);
   else if (p->d.head_dim == 64)
     hipLaunchKernelGGL((bcs_pool_kernel<float, 64>), grid, dim3(256), 0, st, (const float*)src, hl, g,
-                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, assign, (float*)dst);
+                       p->n_buckets, ut.head_stride, ut.row_stride, rows, assign, (float*)dst);
   else
     hipLaunchKernelGGL((bcs_pool_kernel<float, 128>), grid, dim3(256), 0, st, (const float*)src, hl, g,
-                       p->n_buckets, ut.head_stride, ut.row_stride, (int)p->Lc, rows, assign, (float*)dst);
+                       p->n_buckets, ut.head_stride, ut.row_stride, rows, assign, (float*)dst);
   if (int rc = launch_status("bcs_pool_kernel")) return rc;
   if (p->d.n_text > 0) {
     const int cs = chunk_shift(p);
