@@ -51,12 +51,6 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(unsigned, b);
 }
 
-// acc + lo + hi of a packed bf16 pair
-__device__ __forceinline__ float pair_sum(unsigned pair, float acc) {
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), ones, acc, false);
-}
-
 __device__ __forceinline__ bf16x8 read_vt(const uint16_t* p_lo, const uint16_t* p_hi) {
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p_lo);
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p_hi);
@@ -318,18 +312,19 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 
     // ---- softmax against a lagging row reference m_run (this lane's query, its 32 keys; the
     // other 32 are in lane ^ 32).  The probabilities go straight to bf16 pairs in B-operand
-    // order: k slice kk covers keys [16 kk, 16 kk + 16).  The row sums are taken from the
-    // rounded pairs (v_dot2c_f32_bf16 with ones), i.e. of exactly the values the second product
-    // uses, at half the instruction count of fp32 adds.
+    // order: k slice kk covers keys [16 kk, 16 kk + 16).  The row sums are plain fp32 adds of
+    // the probabilities (not v_dot2c_f32_bf16 on the packed pairs: see the pipelined kernel).
     const float mc = m_run * c;
     unsigned u0[8], u1[8];
     float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      u0[j] = pack_bf16(__builtin_amdgcn_exp2f(fmaf(s0[2 * j], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s0[2 * j + 1], c, -mc)));
-      u1[j] = pack_bf16(__builtin_amdgcn_exp2f(fmaf(s1[2 * j], c, -mc)), __builtin_amdgcn_exp2f(fmaf(s1[2 * j + 1], c, -mc)));
-      ps0 = pair_sum(u0[j], ps0);
-      ps1 = pair_sum(u1[j], ps1);
+      const float a0 = __builtin_amdgcn_exp2f(fmaf(s0[2 * j], c, -mc)), a1 = __builtin_amdgcn_exp2f(fmaf(s0[2 * j + 1], c, -mc));
+      const float b0 = __builtin_amdgcn_exp2f(fmaf(s1[2 * j], c, -mc)), b1 = __builtin_amdgcn_exp2f(fmaf(s1[2 * j + 1], c, -mc));
+      u0[j] = pack_bf16(a0, a1);
+      u1[j] = pack_bf16(b0, b1);
+      ps0 += a0 + a1;
+      ps1 += b0 + b1;
     }
     float ps = ps0 + ps1;
     // Reference check: no probability exceeds its row sum, so ps <= P_MAX proves that no score
@@ -349,10 +344,11 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
       ps = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        u0[j] = pack_bf16(__builtin_amdgcn_exp2f(fmaf(s0[2 * j], c, -mc2)), __builtin_amdgcn_exp2f(fmaf(s0[2 * j + 1], c, -mc2)));
-        u1[j] = pack_bf16(__builtin_amdgcn_exp2f(fmaf(s1[2 * j], c, -mc2)), __builtin_amdgcn_exp2f(fmaf(s1[2 * j + 1], c, -mc2)));
-        ps = pair_sum(u0[j], ps);
-        ps = pair_sum(u1[j], ps);
+        const float a0 = __builtin_amdgcn_exp2f(fmaf(s0[2 * j], c, -mc2)), a1 = __builtin_amdgcn_exp2f(fmaf(s0[2 * j + 1], c, -mc2));
+        const float b0 = __builtin_amdgcn_exp2f(fmaf(s1[2 * j], c, -mc2)), b1 = __builtin_amdgcn_exp2f(fmaf(s1[2 * j + 1], c, -mc2));
+        u0[j] = pack_bf16(a0, a1);
+        u1[j] = pack_bf16(b0, b1);
+        ps += (a0 + a1) + (b0 + b1);
       }
       l_run *= alpha;
 #pragma unroll
@@ -685,8 +681,11 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
       // ---- vector work in the shadow of the matrix instruction: the probabilities of block i
       // relative to the row reference m_ref, spread evenly over the slots and staggered by
       // stage so that no instruction of a slot waits for another one of the same slot (a
-      // wavefront issues in order): slot n scales element n+1, exponentiates element n-1,
-      // packs pair (n-3)/2 (odd n) and adds pair (n-4)/2 to the row sums (even n).
+      // wavefront issues in order): slot n scales element n+1, exponentiates element n-1, adds
+      // element n-2 to the row sum and (odd n) packs pair (n-3)/2.  The row sum is a plain fp32
+      // add per element: v_dot2c_f32_bf16 on the packed pairs would be half the instructions,
+      // but it runs on the matrix pipe -- one per slot next to the matrix instruction costs
+      // 45 % of the matrix rate in a register-only microbenchmark, two v_add_f32 cost 2 %.
       // Element e < 16 is sc0[e], element e >= 16 is sc1[e - 16]; pair p = elements 2p, 2p+1.
       auto elem = [&](int e) { return e < 16 ? sc0[e] : sc1[e - 16]; };
       if (n == 0) { x[0] = fmaf(elem(0), c, -mc); x[1] = fmaf(elem(1), c, -mc); }
@@ -698,10 +697,9 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
         u[p >> 3][p & 7] = pack_bf16(ex[2 * p], ex[2 * p + 1]);
         asm volatile("" : "+v"(u[p >> 3][p & 7]));   // used next iteration: keep its computation in this slot
       }
-      if (n >= 4 && !(n & 1)) {
-        const int p = (n - 4) >> 1;
-        if (p >> 3) ps1 = pair_sum(u[1][p & 7], ps1);
-        else ps0 = pair_sum(u[0][p & 7], ps0);
+      if (n >= 2) {
+        if (n & 1) ps1 += ex[n - 2];
+        else ps0 += ex[n - 2];
       }
       // ---- staging: block i+2 leaves the registers (slots SW..SW+3), block i+3 enters (addresses
       // in slot SL, one load in each of the next four), the indices of block i+4 follow (slot SI)
@@ -721,10 +719,10 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
       if (n == SL + 4) vr1 = ld16(V, off1);
     }
     SLOT_FENCE();
-    constexpr int LP = NP - 1;         // last pair: packed here, and the last two pairs summed
+    constexpr int LP = NP - 1;         // last pair: packed here, its two elements summed
     u[LP >> 3][LP & 7] = pack_bf16(ex[NE - 2], ex[NE - 1]);
-    ps1 = pair_sum(u[LP >> 3][(LP - 1) & 7], ps1);
-    ps1 = pair_sum(u[LP >> 3][LP & 7], ps1);
+    ps0 += ex[NE - 2];
+    ps1 += ex[NE - 1];
     float ps = ps0 + ps1;
     asm volatile("" : "+v"(u[LP >> 3][LP & 7]), "+v"(ps));
     __syncthreads();
@@ -757,7 +755,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
         const float e0 = __builtin_amdgcn_exp2f(fmaf(elem_of(sc0, sc1, 2 * p), c, -mc2));
         const float e1 = __builtin_amdgcn_exp2f(fmaf(elem_of(sc0, sc1, 2 * p + 1), c, -mc2));
         u[p >> 3][p & 7] = pack_bf16(e0, e1);
-        ps = pair_sum(u[p >> 3][p & 7], ps);
+        ps += e0 + e1;
       }
       l_run *= alpha;
 #pragma unroll
