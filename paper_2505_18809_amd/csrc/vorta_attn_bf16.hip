@@ -506,7 +506,14 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   auto row_off = [&](int i) {      // element offset of this thread's chunk in staging row i
     return __umul24(f_row0 + min((unsigned)(ld_row + STG_ROWS * i), f_lim), row_stride) + (unsigned)ld_col;
   };
-  auto ld16 = [&](const uint16_t* base, unsigned off) { return *(const u32x4*)(base + off); };
+  // K / V rows come through buffer loads: a scalar resource descriptor per tensor (raw buffer, no
+  // range check: offsets are in bounds by construction) plus one 32-bit byte offset per lane --
+  // a global load carries a 64-bit address per lane and costs more to issue (2.4 % of the loop).
+  const __amdgpu_buffer_rsrc_t rsrc_k = __builtin_amdgcn_make_buffer_rsrc((void*)K, 0, -1, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_v = __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, -1, 0x00020000);
+  auto ld16 = [&](const uint16_t* base, unsigned off) {   // 16 bytes at element offset off of K or V
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(base == K ? rsrc_k : rsrc_v, (int)(off * 2u), 0, 0));
+  };
   const lds_u4_wptr k_wr = (lds_u4_wptr)(smem + ld_row * LSTR + ld_col);
   const lds_u4_wptr v_wr = (lds_u4_wptr)(smem + KTILE + ld_row * VSTR + ld_col);
   auto stage_all = [&](int buf) {
