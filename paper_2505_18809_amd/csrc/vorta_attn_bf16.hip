@@ -34,11 +34,12 @@ constexpr int D = 128;          // head dim
 constexpr int BM = 128;         // query rows per workgroup, window segment (4 wavefronts)
 constexpr int BM_LONG = 256;    // dense and core-set segments (8 wavefronts)
 constexpr int BN = 64;          // keys per LDS block
-// LDS row strides in elements (256 B of data + pad), chosen per access pattern from a
-// bank-conflict microbenchmark: ds_read_b128 of 32 consecutive rows is conflict free at
-// 272 B, the ds_read_b64_tr_b16 pattern (4 rows x 32 B per 16 lanes) at 288 B.
+// LDS row strides in elements (256 B of data + pad), chosen per access pattern with the LDS
+// bank-conflict counter: ds_read_b128 of 32 consecutive rows is conflict free at 272 B; the
+// ds_read_b64_tr_b16 pattern (per instruction 8 rows x 64 B) needs its rows 64 B apart modulo
+// 256 B, i.e. 320 B (at 288 B every such read takes twice the LDS cycles).
 constexpr int LSTR = 136;       // K block and output staging
-constexpr int VSTR = 144;       // V block
+constexpr int VSTR = 160;       // V block
 constexpr int KTILE64 = BN * LSTR;
 constexpr int STAGE64_ELEMS = BN * (LSTR + VSTR);   // one K block + one V block
 constexpr int LDS_BYTES = 2 * STAGE64_ELEMS * 2;
