@@ -510,6 +510,8 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   // K / V rows come through buffer loads: a scalar resource descriptor per tensor (raw buffer, no
   // range check: offsets are in bounds by construction) plus one 32-bit byte offset per lane --
   // a global load carries a 64-bit address per lane and costs more to issue (2.4 % of the loop).
+  // The hardware reads the lane offset as unsigned, so the 2^31 elements a tensor may hold (the
+  // plan's limit) are all within reach; both factors of the row product stay below 2^24.
   const __amdgpu_buffer_rsrc_t rsrc_k = __builtin_amdgcn_make_buffer_rsrc((void*)K, 0, -1, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_v = __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, -1, 0x00020000);
   auto ld16 = [&](const uint16_t* base, unsigned off) {   // 16 bytes at element offset off of K or V
