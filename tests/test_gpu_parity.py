@@ -117,6 +117,34 @@ def test_bcs_index_pool_and_unpool_match_oracle(name, grid, bucket, num, den, dt
     assert (out[1] == 0).all()
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 64)])
+@pytest.mark.parametrize("grid", [(4, 6, 8), (5, 7, 9)])
+@pytest.mark.parametrize("bucket", [(2, 1, 1), (1, 2, 1), (1, 1, 2)])
+def test_two_token_buckets_are_average_pooling(bucket, grid, dtype, d):
+    """The ablation's average-pooling variants (section 4.3) are the core-set route with a bucket
+    of two at ratio 1/2.  Which of the two tokens is the centre is a tie, so a slot's index may be
+    either; what is unique -- the slot every token reads, the pooled rows, the layer's output --
+    is held to the oracle.  On the odd grid the last bucket of the axis is a single token."""
+    cfg = small_cfg("avgpool", grid, 3, dtype, (1, 1, 1), (1, 1, 1), [2, 0, 2], d=d, n_text=5, bucket=bucket)
+    say(f"average pooling {bucket} on {grid} {dtype}")
+    q, k, v = make_qkv(cfg, DEV)
+    plan = vorta.plan_for(cfg)
+    routes = np.array(cfg.fixed_routes, dtype=np.uint8)
+    keep_idx, assign = vorta.vorta_bcs_build_index(plan, k, routes)
+    pooled = vorta.vorta_bcs_pool(plan, v, routes, keep_idx, assign)
+    torch.cuda.synchronize()
+    L = cfg.n_video
+    for slot, h in enumerate([0, 2]):
+        ki, asg, _ = vo.bcs_select(f64(k[h])[:L], grid, bucket, 1, 2)
+        got_ki, got_asg = keep_idx[slot].cpu().numpy(), assign[slot].cpu().numpy()
+        assert np.array_equal(got_asg, asg)
+        assert np.array_equal(got_asg[got_ki], np.arange(len(ki)))           # a slot's index is one of its tokens
+        want = np.concatenate([vo.bcs_pool(f64(v[h])[:L], ki, asg), f64(v[h])[L:]])
+        tol = 2.0 ** -8 * max(1.0, np.abs(want).max()) if dtype == "bf16" else 1e-6
+        assert np.abs(f64(pooled[slot]) - want).max() <= tol
+    check_layer(cfg, cfg.fixed_routes)
+
+
 # ------------------------------------------------------------------ whole layer ----------
 
 def check_layer(cfg, routes, layout=1, rows=None, **plan_over):
