@@ -424,33 +424,31 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 // probability fragments alternate between two register sets from one iteration to the next, so
 // nothing is copied.  One barrier per iteration.
 //
-// Staging (8 wavefronts): K and V rows go from global memory straight into LDS with
-// buffer_load_dwordx4 ... lds -- no staging registers, no LDS write instructions.  Such a load
-// writes the 64 lanes' 16-byte pieces to 1 KiB of consecutive LDS bytes starting at M0, while
-// each lane's global address is free.  A stage therefore holds its 64 rows as 16 groups of four
-// rows (rows j, j+16, j+32, j+48 of the block form group j, 256 B each), one load per group,
-// and the groups are padded apart so that fragment reads stay free of bank conflicts: 1040 B
-// between K groups (ds_read_b128 of 16 consecutive rows), 1088 B between V groups (the
-// ds_read_b64_tr_b16 pattern: four consecutive rows 64 B apart modulo 256 B).  Wavefront w loads
-// groups w and w + 8 of K and of V: four loads per iteration.  K blocks live in a ring of four
-// stages, V blocks in a ring of five: in iteration i, V(i-1) and K(i+1) are read (and, at its
-// end, the first fragments of V(i)), block i+2 is landing and block i+3 is requested.  The loads
-// are inline assembly, invisible to the compiler's wait-count bookkeeping, which would otherwise
-// drain them before every LDS read; the kernel waits itself: before the barrier of iteration i,
-// vmcnt leaves only this iteration's loads outstanding, so block i+2 is in LDS -- two iterations
-// of latency cover.  (The 4-wavefront form stages through registers: global -> registers in
-// iteration i, registers -> LDS in iteration i+1, ring of four K+V stages.)
+// Staging: K and V rows go from global memory straight into LDS with buffer_load_dwordx4 ... lds
+// -- no staging registers, no LDS write instructions.  Such a load writes the 64 lanes' 16-byte
+// pieces to 1 KiB of consecutive LDS bytes starting at M0, while each lane's global address is
+// free.  A stage therefore holds its rows in groups of four, one load per group, and the groups
+// are padded apart so that fragment reads stay free of bank conflicts: 1040 B between K groups
+// (ds_read_b128 wants 16 consecutive rows 16 B apart modulo 256 B), 1088 B between V groups (the
+// ds_read_b64_tr_b16 pattern wants four consecutive rows 64 B apart modulo 256 B).
+//   64-key blocks: rows j, j+16, j+32, j+48 form group j, each row 256 consecutive bytes.
+//   32-key blocks: rows j, j+8, j+16, j+24 form group j; two of them fall among the 16 rows one
+//   ds_read_b128 covers, so the group is stored in 64-byte pieces -- piece (c, G) at 256 c + 64 G,
+//   c = which quarter of the row, G = 0, 2, 1, 3 for the group's first to fourth row.
+// Wavefront w loads groups w and w + NWV of K and of V: four loads per iteration.  K blocks live
+// in a ring of four stages, V blocks in a ring of five: in iteration i, V(i-1) and K(i+1) are
+// read (and, at its end, the first fragments of V(i)), block i+2 is landing and block i+3 is
+// requested.  The loads are inline assembly, invisible to the compiler's wait-count bookkeeping,
+// which would otherwise drain them before every LDS read; the kernel waits itself: before the
+// barrier of iteration i, vmcnt leaves only this iteration's loads outstanding, so block i+2 is
+// in LDS -- two iterations of latency cover.
 // ------------------------------------------------------------------------------------------
 namespace {
-constexpr int KG = 520, VG = 544;        // 8 wavefronts: elements from one four-row group of a K / V stage to the next (1 KiB + pad)
-constexpr int K_STAGE = 16 * KG, V_STAGE = 16 * VG, K_RING = 4, V_RING = 5;
-constexpr int PIPE8_LDS_BYTES = (K_RING * K_STAGE + V_RING * V_STAGE) * 2;
-constexpr int PIPE4_LDS_BYTES = 4 * (STAGE64_ELEMS / 2) * 2;   // 4 wavefronts: ring of four 32-key K+V stages
+constexpr int KG = 520, VG = 544;        // elements from one four-row group of a K / V stage to the next (1 KiB + pad)
+constexpr int K_RING = 4, V_RING = 5;    // stages
+constexpr int pipe_lds_bytes(int nwv) { return (K_RING * KG + V_RING * VG) * (2 * nwv) * 2; }   // 2 nwv groups per stage
 constexpr int LEAD = 2;                  // slots between a fragment request and its use (2..6 measured alike; 2 needs the fewest registers)
 }  // namespace
-
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) u32x4* lds_u4_wptr;
 
 __device__ __forceinline__ float elem_of(const f32x16& t0, const f32x16& t1, int e) { return e < 16 ? t0[e] : t1[e - 16]; }
 
@@ -473,13 +471,10 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   constexpr int NP = NE / 2;                // bf16 pairs of probabilities per lane and block
   constexpr int NKS = KB / 16;              // 16-key k slices of the second product
   static_assert(NWV == 8 || NWV == 4, "8 wavefronts x 64-key blocks or 4 wavefronts x 32-key blocks");
-  constexpr bool DMA = NWV == 8;            // rows go straight to LDS; otherwise through registers
-  constexpr int STG_ROWS = KB / 2;          // through registers: a thread stages rows (tid >> 4) and (tid >> 4) + STG_ROWS
-  constexpr int STAGE_ELEMS = KB * (LSTR + VSTR), KTILE = KB * LSTR;   // through registers: one ring stage = K block, V block
-  constexpr int V_BASE = K_RING * K_STAGE;  // DMA: the K ring, then the V ring
-  constexpr int K_ST = DMA ? K_STAGE : STAGE_ELEMS, V_ST = DMA ? V_STAGE : STAGE_ELEMS;   // elements from a stage to the next
-  constexpr int STG_STEP = DMA ? 8 : STG_ROWS;                                             // rows between a thread's two staging rows
-  auto vstage = [](int b) { return DMA ? (int)((unsigned)b % (unsigned)V_RING) : (b & 3); };   // ring stage of V block b (K: b & 3)
+  constexpr int NG = KB / 4;                // four-row groups per stage: group j holds rows j, j + NG, j + 2 NG, j + 3 NG
+  constexpr int K_STAGE = NG * KG, V_STAGE = NG * VG;   // elements of a K / V stage
+  constexpr int V_BASE = K_RING * K_STAGE;  // the K ring, then the V ring
+  auto vstage = [](int b) { return (int)((unsigned)b % (unsigned)V_RING); };   // ring stage of V block b (K: b & 3)
   const WorkItem w = decode_item<32 * NWV, D>(a, xcd_item(blockIdx.x, gridDim.x, WIN));
   const uint16_t* Q = (const uint16_t*)(w.seg == 0 || WIN ? a.q0 : w.seg == 1 ? a.qc : a.qt) + w.q_off;
   const uint16_t* K = (const uint16_t*)(w.seg == 0 || WIN ? a.k0 : w.seg == 1 ? a.kc : a.kt) + w.kv_off;
@@ -508,15 +503,17 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   for (int r = 0; r < w.n_runs; ++r) n_keys += run_len(r);
   const int n_blocks = (n_keys + KB - 1) / KB;   // dense / core-set: one run
 
-  // ---- staging: a thread moves the 16-byte chunk (lane & 15) of two rows of the block, of K
-  // and of V: rows wave + 16 (lane >> 4) and 8 further when the loads write LDS directly (the
-  // four rows of a group per wavefront and load), rows (tid >> 4) and (tid >> 4) + KB / 2
-  // through registers.  The fetch stream walks the run list one block per call and stays on
+  // ---- staging: a lane moves one 16-byte chunk of two rows of the block, of K and of V: its
+  // wavefront loads groups wave and wave + NWV, and lane p of a load fills bytes 16 p .. 16 p + 15
+  // of the group -- which of the group's four rows (ld_q) and which chunk of that row follows
+  // from the group layout.  The fetch stream walks the run list one block per call and stays on
   // the last block once it is past the end (those extra copies land in ring stages nobody
   // reads), so the loads need no guard.
-  const int ld_row = DMA ? wave + 16 * (lane >> 4) : tid >> 4, ld_col = (tid & 15) * 8;
+  const int ld_q = KB == 64 ? lane >> 4 : 2 * ((lane >> 2) & 1) + ((lane >> 3) & 1);
+  const int ld_chunk = KB == 64 ? lane & 15 : 4 * (lane >> 4) + (lane & 3);
+  const int ld_row = wave + NG * ld_q, ld_col = 8 * ld_chunk;
+  constexpr int STG_STEP = NWV;    // rows from a lane's first staging row to its second
   int fr = 0, fpos = 0, fstart = run_start(0), flen = run_len(0);
-  u32x4 kr0, kr1, vr0, vr1;
   unsigned f_row0 = 0, f_lim = 0;
   auto fetch_cursor = [&]() {      // first row and last valid row offset of the block, then advance
     f_row0 = (unsigned)(fstart + fpos);
@@ -534,19 +531,12 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
     return __umul24(f_row0 + min((unsigned)(ld_row + STG_STEP * i), f_lim), row_stride) + (unsigned)ld_col;
   };
   // K / V rows come through buffer loads: a scalar resource descriptor per tensor (raw buffer, no
-  // range check: offsets are in bounds by construction) plus one 32-bit byte offset per lane --
-  // a global load carries a 64-bit address per lane and costs more to issue (2.4 % of the loop).
+  // range check: offsets are in bounds by construction) plus one 32-bit byte offset per lane.
   // The hardware reads the lane offset as unsigned, so the 2^31 elements a tensor may hold (the
   // plan's limit) are all within reach; both factors of the row product stay below 2^24.
-  const __amdgpu_buffer_rsrc_t rsrc_k = __builtin_amdgcn_make_buffer_rsrc((void*)K, 0, -1, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrc_v = __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, -1, 0x00020000);
-  auto ld16 = [&](const uint16_t* base, unsigned off) {   // 16 bytes at element offset off of K or V
-    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(base == K ? rsrc_k : rsrc_v, (int)(off * 2u), 0, 0));
-  };
-  // Direct form: the same descriptors spelled out as four scalar words for the assembly operand
-  // (base, base high bits with stride 0, no range check, raw 32-bit data format), the LDS byte
-  // address of the ring, and the load: lane p's 16 bytes at element offset off land at
-  // lds_addr + 16 p.  M0 carries the LDS address (one wait state between its write and its use).
+  // The descriptor is four scalar words (base, base high bits with stride 0, no range check, raw
+  // 32-bit data format); lane p's 16 bytes at element offset off land at lds_addr + 16 p.  M0
+  // carries the LDS address (one wait state between its write and its use).
   const unsigned long long k_pa = (unsigned long long)K, v_pa = (unsigned long long)V;
   const i32x4 rs_k = {__builtin_amdgcn_readfirstlane((int)(unsigned)k_pa), __builtin_amdgcn_readfirstlane((int)((unsigned)(k_pa >> 32) & 0xffffu)), -1, 0x00020000};
   const i32x4 rs_v = {__builtin_amdgcn_readfirstlane((int)(unsigned)v_pa), __builtin_amdgcn_readfirstlane((int)((unsigned)(v_pa >> 32) & 0xffffu)), -1, 0x00020000};
@@ -555,17 +545,9 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   auto dma16 = [&](const i32x4& rs, unsigned lds_addr, unsigned off) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(off * 2u), "s"(rs) : "memory", "m0");
   };
-  // group wave + 8 h of K / V block b (h = 0, 1: this thread's first and second staging row)
-  auto dma_k = [&](int h, int b, unsigned off) { dma16(rs_k, lds0 + 2u * (unsigned)((b & 3) * K_STAGE + (wave_u + 8 * h) * KG), off); };
-  auto dma_v = [&](int h, int b, unsigned off) { dma16(rs_v, lds0 + 2u * (unsigned)(V_BASE + vstage(b) * V_STAGE + (wave_u + 8 * h) * VG), off); };
-  const lds_u4_wptr k_wr = (lds_u4_wptr)(smem + ld_row * LSTR + ld_col);
-  const lds_u4_wptr v_wr = (lds_u4_wptr)(smem + KTILE + ld_row * VSTR + ld_col);
-  auto stage_all = [&](int buf) {
-    k_wr[(buf * STAGE_ELEMS) / 8] = kr0;
-    k_wr[(buf * STAGE_ELEMS + STG_ROWS * LSTR) / 8] = kr1;
-    v_wr[(buf * STAGE_ELEMS) / 8] = vr0;
-    v_wr[(buf * STAGE_ELEMS + STG_ROWS * VSTR) / 8] = vr1;
-  };
+  // group wave + NWV h of K / V block b (h = 0, 1: this lane's first and second staging row)
+  auto dma_k = [&](int h, int b, unsigned off) { dma16(rs_k, lds0 + 2u * (unsigned)((b & 3) * K_STAGE + (wave_u + NWV * h) * KG), off); };
+  auto dma_v = [&](int h, int b, unsigned off) { dma16(rs_v, lds0 + 2u * (unsigned)(V_BASE + vstage(b) * V_STAGE + (wave_u + NWV * h) * VG), off); };
   // WIN: token indices of this thread's two staging rows of the NEXT block whose rows will be
   // loaded (gi0, gi1), looked up one block ahead of the rows; win_at / win_idx produce them for
   // the block under the fetch cursor (uniform parameters first, then the per-lane lookup).
@@ -591,7 +573,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
     gi1 = a.tok_of[rows[1]];
   };
   auto win_off = [&](int gi) { return __umul24((unsigned)gi, row_stride) + (unsigned)ld_col; };
-  auto fetch_all = [&](int b) {    // rows of the block under the cursor, block b, into its ring stages (DMA) or the staging registers
+  auto fetch_all = [&](int b) {    // rows of the block under the cursor, block b, into its ring stages
     unsigned o0_, o1_;
     if constexpr (WIN) {
       o0_ = win_off(gi0);
@@ -603,13 +585,8 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
       o0_ = row_off(0);
       o1_ = row_off(1);
     }
-    if constexpr (DMA) {
-      dma_k(0, b, o0_); dma_v(0, b, o0_);
-      dma_k(1, b, o1_); dma_v(1, b, o1_);
-    } else {
-      kr0 = ld16(K, o0_); vr0 = ld16(V, o0_);
-      kr1 = ld16(K, o1_); vr1 = ld16(V, o1_);
-    }
+    dma_k(0, b, o0_); dma_v(0, b, o0_);
+    dma_k(1, b, o1_); dma_v(1, b, o1_);
   };
   // valid keys of the blocks in compute order
   int cr = 0, cpos = 0, clen = flen, cblk = 0;
@@ -635,28 +612,24 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
     win_at();
     win_idx();
   }
-  if constexpr (DMA) {             // blocks 0, 1 and 2 into their stages; iteration i requests block i+3
-    fetch_all(0);
-    fetch_all(1);
-    fetch_all(2);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  } else {
-    fetch_all(0);
-    stage_all(0);
-    fetch_all(1);
-    stage_all(1);
-    fetch_all(2);                    // block 2 waits in registers for iteration 0
-  }
+  fetch_all(0);                    // blocks 0, 1 and 2 into their stages; iteration i requests block i+3
+  fetch_all(1);
+  fetch_all(2);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
-  // Fragment addresses of the lane in stage 0.  DMA layout: row r of a block is at
-  // (r % 16) * group stride + (r / 16) * 256 B.
+  // Fragment addresses of the lane in stage 0 (elements), and what to add for further fragments.
+  // 64-key blocks: row r sits in group r % 16 at (r / 16) * 256 B, chunks in order.
+  // 32-key blocks: row r sits in group r % 8, its quarter c at 256 c + 64 G(r / 8) B, G = 0, 2, 1, 3.
   const int t16 = lane & 15, blk = lane >> 4;
-  const lds_ptr k_rd = DMA ? (lds_ptr)(smem + (l32 & 15) * KG + (l32 >> 4) * 128 + 8 * g) : (lds_ptr)(smem + l32 * LSTR + 8 * g);
-  const lds_ptr v_rd = DMA ? (lds_ptr)(smem + V_BASE + (4 * g + (t16 >> 2)) * VG + 16 * (blk & 1) + 4 * (t16 & 3))
-                           : (lds_ptr)(smem + KTILE + (4 * g + (t16 >> 2)) * VSTR + 16 * (blk & 1) + 4 * (t16 & 3));
-  constexpr int K_T2 = DMA ? 256 : 32 * LSTR;              // second 32-key tile of a block
-  constexpr int V_R16 = DMA ? 128 : 16 * VSTR, V_R8 = DMA ? 8 * VG : 8 * VSTR;   // 16 and 8 rows further
+  const int kq32 = l32 >> 3;                                // 32-key blocks: which row of its group the lane's key row is
+  const lds_ptr k_rd = KB == 64 ? (lds_ptr)(smem + (l32 & 15) * KG + (l32 >> 4) * 128 + 8 * g)
+                                : (lds_ptr)(smem + (l32 & 7) * KG + (2 * (kq32 & 1) + (kq32 >> 1)) * 32 + 8 * g);
+  const lds_ptr v_rd = (lds_ptr)(smem + V_BASE + (4 * g + (t16 >> 2)) * VG + 16 * (blk & 1) + 4 * (t16 & 3));
+  constexpr int K_T2 = 256;                                  // 64-key blocks: second 32-key tile
+  auto k_slice = [](int ks) { return KB == 64 ? 16 * ks : 128 * (ks >> 1) + 16 * (ks & 1); };   // 16 head-dim columns further, ks times
+  constexpr int V_R16 = KB == 64 ? 128 : 32, V_R8 = KB == 64 ? 8 * VG : 64;   // 16 and 8 rows further
+  constexpr int V_C32 = KB == 64 ? 32 : 128;                                   // 32 head-dim columns further
 
   f32x16 o[4], sa0, sa1, sb0, sb1;
 #pragma unroll
@@ -683,8 +656,8 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   // scores of block 0
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
-    sa0 = MFMA(lds_frag3(k_rd + 16 * ks), qf[ks], sa0);
-    if constexpr (KB == 64) sa1 = MFMA(lds_frag3(k_rd + K_T2 + 16 * ks), qf[ks], sa1);
+    sa0 = MFMA(lds_frag3(k_rd + k_slice(ks)), qf[ks], sa0);
+    if constexpr (KB == 64) sa1 = MFMA(lds_frag3(k_rd + K_T2 + k_slice(ks)), qf[ks], sa1);
   }
   {
     const int nv = next_valid();
@@ -695,7 +668,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   // first V^T fragments of the coming iteration, requested before the barrier of this one
   bf16x8 vpre[LEAD];
   auto v_frag = [&](lds_ptr vq, int n) {
-    const lds_ptr ap = vq + V_R16 * (n >> 2) + 32 * (n & 3);
+    const lds_ptr ap = vq + V_R16 * (n >> 2) + V_C32 * (n & 3);
     return read_vt3(ap, ap + V_R8);
   };
 #pragma unroll
@@ -703,15 +676,14 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   // One iteration.  sc*: scores of block i (in), sn*: scores of block i+1 (out),
   // pp: P^T(i-1) (in), pc: P^T(i) (out).
   auto body = [&](int i, f32x16& sc0, f32x16& sc1, f32x16& sn0, f32x16& sn1, bf16x8 (&pp)[NKS], bf16x8 (&pc)[NKS]) {
-    const lds_ptr vq = opaque(v_rd + vstage(i ? i - 1 : 0) * V_ST);
-    const lds_ptr kq = opaque(k_rd + ((i + 1) & 3) * K_ST);
-    const int wbuf = (i + 2) & 3;
+    const lds_ptr vq = opaque(v_rd + vstage(i ? i - 1 : 0) * V_STAGE);
+    const lds_ptr kq = opaque(k_rd + ((i + 1) & 3) * K_STAGE);
     if constexpr (WIN) win_at();                     // block i+4: its token indices are looked up in slot 27
     else fetch_cursor();                             // block i+3 (scalar work and branches: before the slots)
     bf16x8 vf[NPV], kf[NS - NPV];
     auto v_req = [&](int n) { vf[n] = v_frag(vq, n); };
-    auto k_req = [&](int n) { kf[n] = lds_frag3(KB == 64 ? kq + K_T2 * (n & 1) + 16 * (n >> 1) : kq + 16 * n); };
-    const lds_ptr vq_next = opaque(v_rd + vstage(i) * V_ST);     // V(i): second product of iteration i+1
+    auto k_req = [&](int n) { kf[n] = lds_frag3(KB == 64 ? kq + K_T2 * (n & 1) + k_slice(n >> 1) : kq + k_slice(n)); };
+    const lds_ptr vq_next = opaque(v_rd + vstage(i) * V_STAGE);     // V(i): second product of iteration i+1
 #pragma unroll
     for (int n = 0; n < LEAD; ++n) vf[n] = vpre[n];
     float ps0 = 0.f, ps1 = 0.f;
@@ -772,29 +744,18 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
       // ---- staging: the rows of block i+3 are requested (addresses in slot SL, then the four
       // loads SP slots apart: spread over the iteration when nothing precedes them, packed late
       // in it when they use token indices looked up in the previous iteration); the indices of
-      // block i+4 follow (slot SI).  Through registers, block i+2 leaves them first (slots SW..SW+3).
-      constexpr int SW = NS == 32 ? 12 : 4, SL = NS == 32 ? (WIN ? 22 : 8) : 9, SI = NS == 32 ? 27 : 14;
+      // block i+4 follow (slot SI).
+      constexpr int SL = NS == 32 ? (WIN ? 22 : 8) : 9, SI = NS == 32 ? 27 : 14;
       constexpr int SP = WIN ? 1 : 4;
       if (n == SL) {
         off0 = WIN ? win_off(gi0) : row_off(0);
         off1 = WIN ? win_off(gi1) : row_off(1);
       }
       if (WIN && n == SI) win_idx();
-      if constexpr (DMA) {
-        if (n == SL + 1) dma_k(0, i + 3, off0);
-        if (n == SL + 1 + SP) dma_v(0, i + 3, off0);
-        if (n == SL + 1 + 2 * SP) dma_k(1, i + 3, off1);
-        if (n == SL + 1 + 3 * SP) dma_v(1, i + 3, off1);
-      } else {
-        if (n == SW) k_wr[(wbuf * STAGE_ELEMS) / 8] = kr0;
-        if (n == SW + 1) k_wr[(wbuf * STAGE_ELEMS + STG_ROWS * LSTR) / 8] = kr1;
-        if (n == SW + 2) v_wr[(wbuf * STAGE_ELEMS) / 8] = vr0;
-        if (n == SW + 3) v_wr[(wbuf * STAGE_ELEMS + STG_ROWS * VSTR) / 8] = vr1;
-        if (n == SL + 1) kr0 = ld16(K, off0);
-        if (n == SL + 2) vr0 = ld16(V, off0);
-        if (n == SL + 3) kr1 = ld16(K, off1);
-        if (n == SL + 4) vr1 = ld16(V, off1);
-      }
+      if (n == SL + 1) dma_k(0, i + 3, off0);
+      if (n == SL + 1 + SP) dma_v(0, i + 3, off0);
+      if (n == SL + 1 + 2 * SP) dma_k(1, i + 3, off1);
+      if (n == SL + 1 + 3 * SP) dma_v(1, i + 3, off1);
     }
     SLOT_FENCE();
     constexpr int LP = NP - 1;         // last pair: packed here, its two elements summed
@@ -805,7 +766,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
     asm volatile("" : "+v"(u[LP >> 3][LP & 7]), "+v"(ps));
     // all but this iteration's memory operations (four row loads, WIN: and two index lookups) are
     // complete: the rows requested in the previous iteration are in LDS
-    if constexpr (DMA) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WIN ? 6 : 4) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WIN ? 6 : 4) : "memory");
     __syncthreads();
     // ---- reference check.  No probability exceeds its row sum, so ps <= P_MAX proves that no
     // score of the block was more than log2(P_MAX) above the reference.  Otherwise (always for
@@ -867,13 +828,8 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
     // helper wavefront (no query rows: upper half of a split item, or past the last row): it only
     // keeps its share of the staging going, with the same barriers as the others
     for (int i = 0; i < ((n_blocks + 1) & ~1); ++i) {
-      if constexpr (DMA) {
-        fetch_all(i + 3);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WIN ? 6 : 4) : "memory");
-      } else {
-        stage_all((i + 2) & 3);     // block i+2 leaves the registers
-        fetch_all(i + 3);           // block i+3 enters
-      }
+      fetch_all(i + 3);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(WIN ? 6 : 4) : "memory");
       __syncthreads();
     }
   }
@@ -882,12 +838,12 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   // ---- second product of the last iteration's block (its probabilities are in pa)
   {
     const int last = ((n_blocks + 1) & ~1) - 1;
-    const lds_ptr vq = opaque(v_rd + vstage(last) * V_ST);
+    const lds_ptr vq = opaque(v_rd + vstage(last) * V_STAGE);
 #pragma unroll
     for (int n = 0; n < NPV; ++n)
       o[n & 3] = MFMA(n < LEAD ? vpre[n] : v_frag(vq, n), pa[n >> 2], o[n & 3]);
   }
-  if constexpr (DMA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no row load is still on its way into the ring
   __syncthreads();   // every wavefront is done with the ring before stage 0 is reused below
 
   // ---- epilogue: normalise, transpose through LDS, store whole rows
@@ -921,9 +877,9 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   static int attr_rc = VORTA_OK;
   std::call_once(once, [] {
     attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4>, "attn_bf16_kernel<4>", LDS_BYTES);
-    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<false, 8>, "attn_bf16_pipe_kernel<false, 8>", PIPE8_LDS_BYTES);
-    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true, 8>, "attn_bf16_pipe_kernel<true, 8>", PIPE8_LDS_BYTES);
-    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true, 4>, "attn_bf16_pipe_kernel<true, 4>", PIPE4_LDS_BYTES);
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<false, 8>, "attn_bf16_pipe_kernel<false, 8>", pipe_lds_bytes(8));
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true, 8>, "attn_bf16_pipe_kernel<true, 8>", pipe_lds_bytes(8));
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true, 4>, "attn_bf16_pipe_kernel<true, 4>", pipe_lds_bytes(4));
   });
   if (attr_rc) return attr_rc;
   // Long items -- dense heads, core-set heads and the text rows of the window heads, which
@@ -936,7 +892,7 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
     // the last items (at most one per two CUs) go out as half-row items: see AttnArgs::split_from
     const int n_split = std::min(a.end_tile, p->n_cus / 2);
     a.split_from = a.end_tile - n_split;
-    hipLaunchKernelGGL((attn_bf16_pipe_kernel<false, 8>), dim3(a.end_tile + n_split), dim3(512), PIPE8_LDS_BYTES, (hipStream_t)stream, a);
+    hipLaunchKernelGGL((attn_bf16_pipe_kernel<false, 8>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a);
   }
   // Window tiles.  Gathered from the caller's tensors (no tile-ordered copies given): the
   // pipelined kernel again -- tiles of more than 128 tokens in 256-row workgroups of 8
@@ -947,9 +903,9 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   if (a.end_tile > 0 && win_long) {
     const int n_split = std::min(a.end_tile, p->n_cus / 2);
     a.split_from = a.end_tile - n_split;
-    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 8>), dim3(a.end_tile + n_split), dim3(512), PIPE8_LDS_BYTES, (hipStream_t)stream, a);
+    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 8>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a);
   } else if (a.end_tile > 0 && a.win_gather) {
-    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 4>), dim3(a.end_tile), dim3(256), PIPE4_LDS_BYTES, (hipStream_t)stream, a);
+    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 4>), dim3(a.end_tile), dim3(256), pipe_lds_bytes(4), (hipStream_t)stream, a);
   } else if (a.end_tile > 0) {
     hipLaunchKernelGGL((attn_bf16_kernel<4>), dim3(a.end_tile), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
   }
