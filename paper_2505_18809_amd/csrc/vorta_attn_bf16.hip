@@ -429,12 +429,13 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
 // pieces to 1 KiB of consecutive LDS bytes starting at M0, while each lane's global address is
 // free.  A stage therefore holds its rows in groups of four, one load per group, and the groups
 // are padded apart so that fragment reads stay free of bank conflicts: 1040 B between K groups
-// (ds_read_b128 wants 16 consecutive rows 16 B apart modulo 256 B), 1088 B between V groups (the
-// ds_read_b64_tr_b16 pattern wants four consecutive rows 64 B apart modulo 256 B).
+// (ds_read_b128 wants the 16-byte pieces of 32 consecutive rows distinct modulo 512 B), 1088 B
+// between V groups (the ds_read_b64_tr_b16 pattern wants consecutive rows 64 B apart).
 //   64-key blocks: rows j, j+16, j+32, j+48 form group j, each row 256 consecutive bytes.
-//   32-key blocks: rows j, j+8, j+16, j+24 form group j; two of them fall among the 16 rows one
-//   ds_read_b128 covers, so the group is stored in 64-byte pieces -- piece (c, G) at 256 c + 64 G,
-//   c = which quarter of the row, G = 0, 2, 1, 3 for the group's first to fourth row.
+//   32-key blocks: rows j, j+8, j+16, j+24 form group j, and all four fall among the 32 rows one
+//   ds_read_b128 covers, so the group is stored in 128-byte pieces: half h of the group's row q
+//   at 512 h + 128 q.  (With 64-byte pieces at 256 c + 64 G every K read took twice its LDS
+//   cycles, by the bank-conflict counter.)
 // Wavefront w loads groups w and w + NWV of K and of V: four loads per iteration.  K blocks live
 // in a ring of four stages, V blocks in a ring of five: in iteration i, V(i-1) and K(i+1) are
 // read (and, at its end, the first fragments of V(i)), block i+2 is landing and block i+3 is
@@ -509,8 +510,8 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   // from the group layout.  The fetch stream walks the run list one block per call and stays on
   // the last block once it is past the end (those extra copies land in ring stages nobody
   // reads), so the loads need no guard.
-  const int ld_q = KB == 64 ? lane >> 4 : 2 * ((lane >> 2) & 1) + ((lane >> 3) & 1);
-  const int ld_chunk = KB == 64 ? lane & 15 : 4 * (lane >> 4) + (lane & 3);
+  const int ld_q = KB == 64 ? lane >> 4 : (lane >> 3) & 3;
+  const int ld_chunk = KB == 64 ? lane & 15 : 8 * (lane >> 5) + (lane & 7);
   const int ld_row = wave + NG * ld_q, ld_col = 8 * ld_chunk;
   constexpr int STG_STEP = NWV;    // rows from a lane's first staging row to its second
   int fr = 0, fpos = 0, fstart = run_start(0), flen = run_len(0);
@@ -620,16 +621,15 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
 
   // Fragment addresses of the lane in stage 0 (elements), and what to add for further fragments.
   // 64-key blocks: row r sits in group r % 16 at (r / 16) * 256 B, chunks in order.
-  // 32-key blocks: row r sits in group r % 8, its quarter c at 256 c + 64 G(r / 8) B, G = 0, 2, 1, 3.
+  // 32-key blocks: row r sits in group r % 8, half h of it at 512 h + 128 (r / 8) B.
   const int t16 = lane & 15, blk = lane >> 4;
-  const int kq32 = l32 >> 3;                                // 32-key blocks: which row of its group the lane's key row is
   const lds_ptr k_rd = KB == 64 ? (lds_ptr)(smem + (l32 & 15) * KG + (l32 >> 4) * 128 + 8 * g)
-                                : (lds_ptr)(smem + (l32 & 7) * KG + (2 * (kq32 & 1) + (kq32 >> 1)) * 32 + 8 * g);
+                                : (lds_ptr)(smem + (l32 & 7) * KG + (l32 >> 3) * 64 + 8 * g);
   const lds_ptr v_rd = (lds_ptr)(smem + V_BASE + (4 * g + (t16 >> 2)) * VG + 16 * (blk & 1) + 4 * (t16 & 3));
   constexpr int K_T2 = 256;                                  // 64-key blocks: second 32-key tile
-  auto k_slice = [](int ks) { return KB == 64 ? 16 * ks : 128 * (ks >> 1) + 16 * (ks & 1); };   // 16 head-dim columns further, ks times
-  constexpr int V_R16 = KB == 64 ? 128 : 32, V_R8 = KB == 64 ? 8 * VG : 64;   // 16 and 8 rows further
-  constexpr int V_C32 = KB == 64 ? 32 : 128;                                   // 32 head-dim columns further
+  auto k_slice = [](int ks) { return KB == 64 ? 16 * ks : 16 * (ks & 3) + 256 * (ks >> 2); };   // head-dim columns 16 ks ..
+  auto v_cols = [](int cb) { return KB == 64 ? 32 * cb : 32 * (cb & 1) + 256 * (cb >> 1); };     // head-dim columns 32 cb ..
+  constexpr int V_R16 = 128, V_R8 = KB == 64 ? 8 * VG : 64;  // 16 and 8 rows further
 
   f32x16 o[4], sa0, sa1, sb0, sb1;
 #pragma unroll
@@ -668,7 +668,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   // first V^T fragments of the coming iteration, requested before the barrier of this one
   bf16x8 vpre[LEAD];
   auto v_frag = [&](lds_ptr vq, int n) {
-    const lds_ptr ap = vq + V_R16 * (n >> 2) + V_C32 * (n & 3);
+    const lds_ptr ap = vq + V_R16 * (n >> 2) + v_cols(n & 3);
     return read_vt3(ap, ap + V_R8);
   };
 #pragma unroll
