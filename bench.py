@@ -27,8 +27,8 @@ METRIC = "ms per routed attention layer + effective TFLOP/s (% MFMA peak) at 75.
 MFMA_PEAK_TFLOPS = {"bf16": 2516.6, "fp32": 157.3}      # MI355X dense peaks
 # HBM bytes per launch of the dominant kernel on the wan720p workload, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs of this command, each scaled by what the counter reads for a
-# plain 1 GiB copy (profiles/layer_wan720p_hbm_traffic.txt): (8,586,844 + 264,600) KiB.
-ATTN_TRAFFIC_BYTES = (8586844 + 264600) * 1024
+# plain 1 GiB copy (profiles/layer_wan720p_hbm_traffic.txt): (8,589,710 + 264,600) KiB.
+ATTN_TRAFFIC_BYTES = (8589710 + 264600) * 1024
 
 
 def layer_flops(cfg, plan, routes):
