@@ -240,6 +240,18 @@ def main():
         torch.cuda.synchronize()
         dom = {"kernel": "attn_bf16_pipe_kernel<false, 8>", "ms": e0.elapsed_time(e1) / args.steps,
                "flops": per_route[0] + per_route[2]}
+        # The same launch on all-zero operands: the same instructions and cycle count, but no
+        # operand bit toggles, so the power limit does not hold the clock down.  A diagnostic
+        # of what the limit costs on real data, not a throughput claim.
+        for t in (sq, sk, sv) + ((sbuf(4), sbuf(5), sbuf(6)) if n_lr else ()):
+            t.zero_()
+        vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
+        e0.record()
+        for _ in range(3):
+            vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
+        e1.record()
+        torch.cuda.synchronize()
+        dom["zero_ms"] = e0.elapsed_time(e1) / 3
         del sq, sk, sv, so, sws
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
     result = {
@@ -262,6 +274,11 @@ def main():
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "flops_per_launch": dom["flops"], "ms_per_launch": dom["ms"],
                      "traffic": ATTN_TRAFFIC_BYTES if args.workload == "wan720p" else None},
+        "dominant_kernel_on_zero_operands": ({"ms_per_launch": dom["zero_ms"],
+                                              "TFLOP/s": dom["flops"] / (dom["zero_ms"] * 1e-3) / 1e12,
+                                              "frac": dom["flops"] / (dom["zero_ms"] * 1e-3) / 1e12 / peak,
+                                              "note": "same launch, all-zero Q/K/V: same cycle count, clock not held down by the power limit"}
+                                             if "zero_ms" in dom else None),
         "stages_ms": stage_ms,
         # the attention call is two launches; the window launch is what the dominant kernel leaves of it
         "attention_launches": {
