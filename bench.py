@@ -121,6 +121,8 @@ def main():
     ap.add_argument("--workload", default="wan720p")
     ap.add_argument("--layout", type=int, default=1, help="1 = [heads][N][d], 0 = [N][heads][d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="also time the dominant kernel's launch on all-zero Q/K/V (what the power limit costs on real data)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -243,15 +245,17 @@ def main():
         # The same launch on all-zero operands: the same instructions and cycle count, but no
         # operand bit toggles, so the power limit does not hold the clock down.  A diagnostic
         # of what the limit costs on real data, not a throughput claim.
-        for t in (sq, sk, sv) + ((sbuf(4), sbuf(5), sbuf(6)) if n_lr else ()):
-            t.zero_()
-        vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
-        e0.record()
-        for _ in range(3):
+        # Off by default, so that a profile of the default command holds launches of one kind.
+        if args.zero_operands:
+            for t in (sq, sk, sv) + ((sbuf(4), sbuf(5), sbuf(6)) if n_lr else ()):
+                t.zero_()
             vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
-        e1.record()
-        torch.cuda.synchronize()
-        dom["zero_ms"] = e0.elapsed_time(e1) / 3
+            e0.record()
+            for _ in range(3):
+                vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
+            e1.record()
+            torch.cuda.synchronize()
+            dom["zero_ms"] = e0.elapsed_time(e1) / 3
         del sq, sk, sv, so, sws
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
     result = {
