@@ -479,3 +479,50 @@ def test_full_size_layer_on_sampled_rows(name):
         assert err <= TOL[cfg.dtype], f"{name} head {h} route {r}: {err}"
     assert torch.isfinite(out.float()).all()
     say(f"{name}: worst max-abs per route {worst}")
+
+
+@pytest.mark.parametrize("tile", [(4, 4, 6), (4, 8, 6)])
+def test_largest_tensors_a_plan_accepts(tile):
+    """131,071 tokens x 128 heads x 128 = 2^31 - 16,384 elements per tensor (4 GiB in bf16), the
+    most a plan takes, in the token-major layout, where every head's rows are spread over the
+    whole tensor: the 32-bit element and byte offsets of the kernels run up to their limits.
+    Tiles of 96 and of 192 tokens take the 4- and the 8-wavefront window kernel.  The first and
+    the last heads of every route are held to the oracle on sampled rows, the last rows among
+    them; the 31-frame grid is divided by neither the tile nor the bucket."""
+    heads = vorta.VORTA_MAX_HEADS if hasattr(vorta, "VORTA_MAX_HEADS") else 128
+    routes = np.array([0, 1, 2] + [1, 2] * 61 + [2, 1, 0], dtype=np.uint8)
+    assert len(routes) == heads == 128
+    cfg = small_cfg("largest", (31, 64, 66), heads, "bf16", tile, (3, 3, 3), routes.tolist(), n_text=127, seed=23)
+    N, L = cfg.n_tokens, cfg.n_video
+    assert N * heads * 128 == 2 ** 31 - 16384
+    say(f"largest tile {tile}: generating {3 * N * heads * 128 * 2 / 2 ** 30:.1f} GiB of inputs")
+    q, k, v = make_qkv(cfg, DEV, layout=0)
+    plan = vorta.plan_for(cfg, layout=0)
+    ws = torch.empty(vorta.vorta_workspace_bytes(plan, routes), dtype=torch.uint8, device=DEV)
+    out = vorta.vorta_routed_attention_layer(plan, q, k, v, routes, workspace=ws)
+    torch.cuda.synchronize()
+    say("largest: layer done, checking against the oracle")
+    off = vorta.vorta_workspace_layout(plan, routes)
+    n_lr = int((routes == 2).sum())
+    keep_idx = ws[off[8]: off[8] + n_lr * plan.n_core * 4].view(torch.int32).view(n_lr, plan.n_core)
+    assign = ws[off[9]: off[9] + n_lr * plan.n_video * 4].view(torch.int32).view(n_lr, plan.n_video)
+    spec = spec_of(cfg)
+    rng = np.random.default_rng(cfg.seed)
+    rows = np.unique(np.concatenate([rng.choice(L, 48, replace=False), [0, L - 2, L - 1, L, N - 2, N - 1]]))
+    lr_slot_of = {int(h): i for i, h in enumerate(np.nonzero(routes == 2)[0])}
+    for h in (0, 1, 2, 125, 126, 127):
+        r = int(routes[h])
+        Q, K, V = f64(q[:, h]), f64(k[:, h]), f64(v[:, h])
+        if r == 2:
+            ki, asg, gap = vo.bcs_select(K[:L], cfg.grid, cfg.bucket, cfg.keep_num, cfg.keep_den)
+            assert gap > 1e-12
+            slot = lr_slot_of[h]
+            assert np.array_equal(keep_idx[slot].cpu().numpy(), ki) and np.array_equal(assign[slot].cpu().numpy(), asg), f"head {h}"
+            want = vo.coreset_attention(Q, K, V, spec, rows, index=(ki, asg))
+        else:
+            want = vo.head_attention(r, Q, K, V, spec, rows)
+        got = f64(out[:, h][torch.as_tensor(rows, device=DEV)])
+        err = np.abs(got - want).max()
+        say(f"  largest head {h:3d} route {r}: {len(rows)} rows, max-abs {err:.3e}")
+        assert err <= TOL["bf16"], f"head {h} route {r}: {err}"
+    assert torch.isfinite(out[-1024:].float()).all() and torch.isfinite(out[:1024].float()).all()
