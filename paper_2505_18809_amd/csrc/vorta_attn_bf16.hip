@@ -741,13 +741,16 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
         if (n & 1) ps1 += ex[n - 2];
         else ps0 += ex[n - 2];
       }
-      // ---- staging: the rows of block i+3 are requested (addresses in slot SL, then the four
-      // loads SP slots apart: spread over the iteration when nothing precedes them, packed late
-      // in it when they use token indices looked up in the previous iteration); the indices of
-      // block i+4 follow (slot SI).
-      constexpr int SL = NS == 32 ? (WIN ? 22 : 8) : 9, SI = NS == 32 ? 27 : 14;
-      constexpr int SP = WIN ? 1 : 4;
-      if (n == SL) {
+      // ---- staging: the rows of block i+3 are requested -- addresses in slot SO, the four loads
+      // from slot SL + 1 on, SP slots apart -- and (WIN) the token indices of block i+4 looked up
+      // in slot SI.  32 slots: the loads are spread over the iteration, and the lookup comes
+      // right after the addresses, which were the last use of the indices it replaces, so that
+      // it has almost a whole iteration to return (window launch of 432-token tiles -3 %
+      // against loads packed into slots 23..26 and the lookup in slot 27).  16 slots: placement
+      // made no difference; loads packed late, lookup after them.
+      constexpr int SL = NS == 32 ? 8 : 9, SP = NS == 32 ? 4 : 1;
+      constexpr int SO = NS == 32 ? (WIN ? 1 : SL) : SL, SI = NS == 32 ? 2 : 14;
+      if (n == SO) {
         off0 = WIN ? win_off(gi0) : row_off(0);
         off1 = WIN ? win_off(gi1) : row_off(1);
       }
