@@ -186,7 +186,7 @@ def test_ragged_shapes_text_tokens_and_mixed_routes(dtype, d):
     check_layer(cfg, cfg.fixed_routes, layout=0)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(64))
 def test_seeded_random_small_layers(seed):
     """Shapes drawn from a seed: grids that make ragged last blocks, one- and many-run windows,
     run lists crossing 64-key blocks, tiles above and below a query block, text tokens or none,
