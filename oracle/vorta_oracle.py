@@ -224,7 +224,9 @@ def bcs_buckets(grid, bucket):
 
 
 def bcs_prune_count(bucket_size: int, keep_num: int, keep_den: int) -> int:
-    """k = floor(B' (1 - r)), never pruning the centre itself."""
+    """k = floor(B' (1 - r)), never pruning the centre itself.  r = keep_num / keep_den is the
+    share of the sequence that STAYS (section 4.3: the core-set at r_core = 50 % has half the
+    original length, and larger ratios cost more computation)."""
     return min(bucket_size - 1, (bucket_size * (keep_den - keep_num)) // keep_den)
 
 

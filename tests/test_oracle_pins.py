@@ -237,7 +237,28 @@ def test_bcs_fig3_counts_and_centre():
         assert len(buckets) == 1
         idx, c = buckets[0]
         assert c == centre and list(idx) == list(range(bf * bh * bw))
-        assert vo.bcs_prune_count(bf * bh * bw, num, den) == k
+        B = bf * bh * bw
+        assert vo.bcs_prune_count(B, num, den) == k
+        # the selection itself keeps B - k tokens and sends exactly k others to the centre's slot
+        feat = np.random.default_rng(B + num).standard_normal((B, 6))
+        keep_idx, assign, _ = vo.bcs_select(feat, (bf, bh, bw), (bf, bh, bw), num, den)
+        assert len(keep_idx) == B - k and centre in keep_idx
+        assert int((assign == assign[centre]).sum()) == k + 1
+
+
+@pytest.mark.parametrize("num,den", [(1, 4), (1, 3), (1, 2), (2, 3), (3, 4)])
+def test_core_set_length_is_the_kept_share_of_the_sequence(num, den):
+    """r_core is the share of the sequence that stays in the core-set (section 4.3: at 50 % the
+    core-set is half the original length, and larger ratios cost more computation): on a grid of
+    whole 12-token buckets L_c = r L, and a larger r keeps a superset of a smaller one's tokens."""
+    grid, bucket = (4, 6, 6), (2, 3, 2)
+    L = 4 * 6 * 6
+    feat = smooth_field(np.random.default_rng(21), grid, 6)
+    keep_idx, assign, _ = vo.bcs_select(feat, grid, bucket, num, den)
+    assert len(keep_idx) * den == L * num
+    assert len(set(assign)) == len(keep_idx)
+    more, _, _ = vo.bcs_select(feat, grid, bucket, min(num + 1, den), den)
+    assert set(keep_idx) <= set(more)
 
 
 def test_bcs_buckets_partition_the_grid_and_clip_at_border():
@@ -354,8 +375,9 @@ def test_bcs_with_two_token_buckets_is_average_pooling(axis, bucket):
     np.testing.assert_allclose(vo.bcs_unpool(Xc, assign), up, atol=1e-14)
 
 
-def scalar_coreset(Q, K, V, grid, bucket, scale, n_text=0):
-    """Core-set route re-derived with Python scalars only, from section 3.2."""
+def scalar_coreset(Q, K, V, grid, bucket, scale, n_text=0, keep=(1, 2)):
+    """Core-set route re-derived with Python scalars only, from section 3.2.  keep = r_core as a
+    fraction: of a bucket's B tokens, B - floor(B (1 - r)) stay (never fewer than the centre)."""
     F, H, W = grid
     L, d = F * H * W, len(Q[0])
     dot = lambda a, b: sum(x * y for x, y in zip(a, b))
@@ -373,7 +395,8 @@ def scalar_coreset(Q, K, V, grid, bucket, scale, n_text=0):
                     if t != c:
                         den = math.sqrt(dot(K[c], K[c]) * dot(K[t], K[t]))
                         sims.append((-(dot(K[c], K[t]) / den if den else 0.0), t))
-                k = min(len(toks) - 1, len(toks) // 2)
+                n_stay = max(1, len(toks) - (len(toks) * (keep[1] - keep[0])) // keep[1])
+                k = len(toks) - n_stay
                 dropped = [t for _, t in sorted(sims)[:k]]
                 for t in toks:
                     if t not in dropped:
@@ -388,13 +411,15 @@ def scalar_coreset(Q, K, V, grid, bucket, scale, n_text=0):
     return out
 
 
-@pytest.mark.parametrize("grid,n_text", [((2, 3, 4), 0), ((3, 4, 3), 2)])
-def test_coreset_route_matches_scalar_rederivation(grid, n_text):
+@pytest.mark.parametrize("grid,n_text,keep", [((2, 3, 4), 0, (1, 2)), ((3, 4, 3), 2, (1, 2)),
+                                              ((2, 3, 4), 1, (1, 4)), ((3, 4, 3), 0, (3, 4)), ((2, 6, 2), 2, (2, 3))])
+def test_coreset_route_matches_scalar_rederivation(grid, n_text, keep):
     rng = np.random.default_rng(11)
     L = grid[0] * grid[1] * grid[2]
     Q, K, V = (np.concatenate([smooth_field(rng, grid, 5), rng.standard_normal((n_text, 5))]) for _ in range(3))
-    spec = vo.LayerSpec(grid=grid, tile=(1, 1, 1), window=(1, 1, 1), n_text=n_text, scale=0.4)
-    want = scalar_coreset(Q.tolist(), K.tolist(), V.tolist(), grid, (2, 3, 2), 0.4, n_text)
+    spec = vo.LayerSpec(grid=grid, tile=(1, 1, 1), window=(1, 1, 1), n_text=n_text, scale=0.4,
+                        keep_num=keep[0], keep_den=keep[1])
+    want = scalar_coreset(Q.tolist(), K.tolist(), V.tolist(), grid, (2, 3, 2), 0.4, n_text, keep)
     got = vo.coreset_attention(Q, K, V, spec)
     np.testing.assert_allclose(got, want, atol=1e-13)
     np.testing.assert_allclose(vo.coreset_attention(Q, K, V, spec, rows=[L + n_text - 1, 3, 0]),
