@@ -86,10 +86,11 @@ def cpu_baseline(cfg, q, k, v, routes, total_flops, per_head_flops, counts, budg
             "sample": "fp64 NumPy oracle, " + "; ".join(sample) + "; per-row time scaled to all rows and heads"}
 
 
-def mfma_probe(vorta, torch, dev):
+def mfma_probe(torch, dev):
     """Matrix-pipe rate with nothing else running, per operand distribution (context for the
     roofline fraction: the nominal peak assumes the nominal clock, the sustained clock depends
     on how many operand bits toggle)."""
+    from paper_2505_18809_amd import probe
     out = {}
     gen = torch.Generator(device="cpu").manual_seed(1)
     kinds = {
@@ -100,11 +101,11 @@ def mfma_probe(vorta, torch, dev):
     for name, vals in kinds.items():
         ops = vals.to(torch.bfloat16).to(dev)
         iters, wgs = 4000, 256 * 4
-        vorta.vorta_probe_mfma_rate(ops, 200, wgs)            # warm-up
+        probe.mfma_probe_rate(ops, 200, wgs)            # warm-up
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        flops, _, clocks = vorta.vorta_probe_mfma_rate(ops, iters, wgs)
+        flops, _, clocks = probe.mfma_probe_rate(ops, iters, wgs)
         e1.record()
         torch.cuda.synchronize()
         c = clocks.cpu().tolist()
@@ -314,7 +315,7 @@ def main():
         "memory_passes_GBps": {n: pass_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in pass_bytes if stage_ms.get(n, 0) > 0},
     }
     if cfg.dtype == "bf16":
-        result["mfma_probe"] = mfma_probe(vorta, torch, dev)
+        result["mfma_probe"] = mfma_probe(torch, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, q if args.layout == 1 else q.transpose(0, 1),
                                               k if args.layout == 1 else k.transpose(0, 1),

@@ -25,7 +25,9 @@
  *     device call on a plan uploads the plan's small index tables with a
  *     blocking hipMalloc + hipMemcpy (a few hundred KB, once per plan) on the
  *     device that is current then; the plan belongs to that device from then on
- *     (a device call with another device current returns VORTA_EINVAL).
+ *     (a device call with another device current returns VORTA_EINVAL).  Call
+ *     vorta_plan_upload beforehand to have that done at a time of your choosing
+ *     (needed before the first call under graph capture).
  *   - Return value: VORTA_OK or a negative error code; vorta_last_error() has
  *     a thread-local message.  Nothing is printed, thrown or aborted.  Invalid
  *     arguments are rejected before any kernel is launched.
@@ -45,7 +47,7 @@ extern "C" {
 enum {
   VORTA_OK = 0,
   VORTA_EINVAL = -1,      /* null pointer, bad enum value                                  */
-  VORTA_ESHAPE = -2,      /* grid not divisible by tile, window/bucket < 1, head_dim unsupported */
+  VORTA_ESHAPE = -2,      /* grid, tile, window or bucket < 1, head_dim unsupported, too many tokens */
   VORTA_EDTYPE = -3,
   VORTA_EWORKSPACE = -4,  /* workspace smaller than vorta_workspace_bytes                   */
   VORTA_EROUTE = -5,      /* a route code above 2                                          */
@@ -56,7 +58,13 @@ enum {
 enum { VORTA_ROUTE_FULL = 0, VORTA_ROUTE_WINDOW = 1, VORTA_ROUTE_CORESET = 2 };
 enum { VORTA_F32 = 0, VORTA_BF16 = 1 };
 enum { VORTA_LAYOUT_NHD = 0, VORTA_LAYOUT_HND = 1 };
-enum { VORTA_CENTER_CLAMP = 0, VORTA_CENTER_IDENTITY = 1 };
+/* Readings of Algorithm 1's get_window_center_id (named there, not defined), per axis, for query
+ * tile q of n tiles under a window of w tiles:
+ *   CLAMP     min(max(q, w/2), max(n - 1 - w/2, w/2)): the window slides but stays inside the grid
+ *   IDENTITY  q: the window is cut off at the border
+ *   BLOCK     (q / w) w + w/2: the tile grid is cut into blocks of w tiles whose query tiles all
+ *             share the block's middle tile (section 3.2's tau(i) taken per axis on tile ids)   */
+enum { VORTA_CENTER_CLAMP = 0, VORTA_CENTER_IDENTITY = 1, VORTA_CENTER_BLOCK = 2 };
 
 #define VORTA_MAX_HEADS 128
 
@@ -69,10 +77,12 @@ typedef struct vorta_layer_desc {
   int32_t dtype;            /* VORTA_F32 | VORTA_BF16 (inputs, outputs and internal buffers) */
   int32_t layout;           /* VORTA_LAYOUT_*                                                */
   int32_t tile[3];          /* tokens per tile (t_F, t_H, t_W) >= 1; where a tile does not divide
-                               the grid axis, the last tile of that axis is clipped to the grid */
+                               the grid axis, the last tile of that axis is clipped to the grid
+                               (a tile larger than the axis is the whole axis)                */
   int32_t window[3];        /* window in TILES, the unit Algorithm 1 compares; >= 1          */
   int32_t center_mode;      /* VORTA_CENTER_*: how get_window_center_id treats border tiles  */
-  int32_t bucket[3];        /* BCS bucket, the paper uses (2,3,2); border buckets are clipped */
+  int32_t bucket[3];        /* BCS bucket, the paper uses (2,3,2); border buckets are clipped;
+                               at most 64 tokens after clipping to the grid                    */
   int32_t keep_num, keep_den; /* core-set ratio r = keep_num/keep_den, 0 < r <= 1 (paper: 1/2) */
   float softmax_scale;      /* <= 0 selects 1/sqrt(head_dim)                                 */
 } vorta_layer_desc;
@@ -105,6 +115,13 @@ const char* vorta_last_error(void);     /* thread-local, valid until the thread'
  * VORTA_ESHAPE. */
 int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out);
 int vorta_plan_destroy(vorta_plan* plan);
+
+/* Set-up step for callers that want no allocation later: uploads the plan's index tables now
+ * (blocking hipMalloc + hipMemcpy on the current device, which the plan then belongs to) instead
+ * of on the first device call.  Idempotent.  After it, no entry point allocates device memory
+ * for this plan. */
+int vorta_plan_upload(vorta_plan* plan);
+
 int vorta_plan_info_get(const vorta_plan* plan, vorta_plan_info* out);
 
 /* ---- host tables: deterministic integers, checkable without a GPU ----------------------- */
@@ -150,6 +167,18 @@ int vorta_router_gates(const float* t_emb, const float* w_r, int32_t d_t, int32_
  * taken only if its gate strictly exceeds both others, every tie goes to full.  Host arrays. */
 int vorta_route_select(const float* alpha_host, int32_t heads, uint8_t* routes_host);
 
+/* Eq. 3 and Eq. 4 on the device for a whole sampling schedule in one launch (the gates depend on
+ * the timestep embedding only, section 3.3 "Attention router", so the routes of every step can be
+ * had before sampling starts).  t_emb: device float[n_steps][d_t]; w_r: device
+ * float[heads][d_t][3]; alpha: device float[n_steps][heads][3] (out); routes: device
+ * uint8[n_steps][heads] (out).  Logits, softmax and the comparison of Eq. 4 are fp64 (ties go to
+ * full attention), the gates are stored rounded to fp32.  routes_host, if not NULL, receives a
+ * copy of `routes` through an asynchronous device-to-host copy on `stream` (pinned host memory
+ * keeps it asynchronous): synchronise the stream before reading it -- the layer call takes its
+ * routes from the host.  n_steps <= 65535.  Allocates nothing. */
+int vorta_router_device(const float* t_emb, const float* w_r, int32_t n_steps, int32_t d_t, int32_t heads,
+                        float* alpha, uint8_t* routes, uint8_t* routes_host, void* stream);
+
 /* ---- device passes ------------------------------------------------------------------------ */
 
 /* Token reorder, raster order -> tile order, for the heads on route 1 (Algorithm 1 needs
@@ -163,15 +192,20 @@ int vorta_reorder_to_tiles(vorta_plan* plan, const void* src, const uint8_t* rou
 int vorta_reorder_from_tiles(vorta_plan* plan, const void* src, const uint8_t* routes_host,
                              void* dst, void* stream);
 
-/* Bucketed core-set selection for the heads on route 2 (section 3.2, Fig. 3).  feat: user
- * layout feature tensor (the layer call passes K).  Per bucket: cosine similarity (fp64) of
+/* Bucketed core-set selection for the heads on route 2 (section 3.2, Fig. 3).  feat: the feature
+ * the similarity is taken on, head_dim elements per token.  feat_head_stride says how it is laid
+ * out: VORTA_FEAT_USER_LAYOUT = a tensor in the user layout (the layer call passes K this way);
+ * 0 = ONE array [L][head_dim] shared by every head (the core-set equation pools the block's
+ * input, which has no head axis: all heads then select the same tokens); s > 0 = [heads][.][head_dim]
+ * with s >= L * head_dim elements from one head to the next.  Per bucket: cosine similarity (fp64) of
  * the centre token to every other token, the k = floor(B (1 - r)) most similar are pruned
  * (ties: smaller local raster index first).  Outputs, slot-major:
  *   keep_idx int32[n_lr][L_c]  raster index of the token in each core-set slot
  *   assign   int32[n_lr][L]    slot each token reads its output from (own slot if kept,
  *                              its bucket centre's slot if pruned). */
-int vorta_bcs_build_index(vorta_plan* plan, const void* feat, const uint8_t* routes_host,
-                          int32_t* keep_idx, int32_t* assign, void* stream);
+#define VORTA_FEAT_USER_LAYOUT (-1)
+int vorta_bcs_build_index(vorta_plan* plan, const void* feat, int64_t feat_head_stride,
+                          const uint8_t* routes_host, int32_t* keep_idx, int32_t* assign, void* stream);
 
 /* pool(): dst[slot][s] = mean of src rows assigned to core-set slot s (a kept token alone,
  * or a centre with the tokens pruned into it), then the text rows unchanged.  src: user
@@ -200,23 +234,13 @@ typedef struct vorta_attn_io {
 int vorta_attention_routed(vorta_plan* plan, const uint8_t* routes_host,
                            const vorta_attn_io* io, void* stream);
 
-/* Back to sequence order: route 1 rows by the inverse tile permutation from o_t (skipped when
- * o_t is NULL: see vorta_attn_io), route 2
- * rows by unpool() -- out[i] = o_c[assign[i]], text rows from o_c[L_c + t] -- into the
- * user-layout out.  Route 0 rows are already in place. */
+/* Back to sequence order (section 3.2: the sliding-tile branch computes on tile-contiguous
+ * tokens, the core-set branch ends with unpool()): route 1 rows by the inverse tile permutation
+ * from o_t (bf16 only: skipped when o_t is NULL, see vorta_attn_io; with fp32 a NULL o_t while
+ * heads take route 1 is VORTA_EINVAL), route 2 rows by unpool() -- out[i] = o_c[assign[i]], text
+ * rows from o_c[L_c + t] -- into the user-layout out.  Route 0 rows are already in place. */
 int vorta_scatter_back(vorta_plan* plan, const uint8_t* routes_host, const void* o_t,
                        const void* o_c, const int32_t* assign, void* out, void* stream);
-
-/* ---- measurement aid ------------------------------------------------------------------------ */
-
-/* Not a step of the method: runs only v_mfma_f32_32x32x16_bf16 (8 wavefronts per workgroup,
- * `workgroups` workgroups, `iters` x 32 instructions per wavefront) on the operand bits the
- * caller supplies, so that bench.py can report the matrix rate the chip sustains for a given
- * data distribution next to the nominal peak.  operands: device, 16 x 64 x 16 bytes (8 A and 8 B
- * fragments per lane); sink: device float[workgroups * 512]; clocks: device int64[2], receives
- * shader-clock ticks and 100 MHz ticks of workgroup 0.  FLOPs = workgroups*8*iters*32*32768. */
-int vorta_probe_mfma_rate(const void* operands, int32_t iters, int32_t workgroups, void* sink,
-                          void* clocks, void* stream);
 
 /* ---- the whole path ----------------------------------------------------------------------- */
 
@@ -228,15 +252,23 @@ int vorta_workspace_bytes(const vorta_plan* plan, const uint8_t* routes_host, si
  * q_t,k_t,v_t,o_t,q_c,k_c,v_c,o_c,keep_idx,assign (for inspection by tests). */
 int vorta_workspace_layout(const vorta_plan* plan, const uint8_t* routes_host, size_t offsets[10]);
 
-/* reorder + index build + pool + fused attention + scatter back, all on `stream`:
- * q, k, v (user layout) -> out (user layout).  The BCS feature is K. */
+/* One attention layer under hard routing (Eq. 4; section 3.3 "Inference-time routing
+ * strategy"): every head runs the branch its route names -- Eq. 2, Algorithm 1 or the core-set
+ * branch of section 3.2.  reorder + index build + pool + fused attention + scatter back, all on
+ * `stream`: q, k, v (user layout) -> out (user layout).  The BCS feature is K. */
 int vorta_routed_attention_layer(vorta_plan* plan, const void* q, const void* k, const void* v,
                                  const uint8_t* routes_host, void* out, void* workspace,
                                  size_t workspace_bytes, void* stream);
 
 /* Eq. 5 (router optimisation forward): every head runs all three branches and the outputs
  * are blended with its gates, out = a1 attn + a2 sliding + a3 coreset.  alpha_host:
- * host float[heads][3].  workspace: vorta_soft_mixture_workspace_bytes. */
+ * host float[heads][3].  workspace: vorta_soft_mixture_workspace_bytes.
+ * bf16: fused -- the core-set branch leaves its pooled output rows in the workspace, the
+ * sliding-tile branch writes the video rows of `out`, and the epilogue of the full-attention
+ * branch reads both and writes the gate-weighted sum (fp32 arithmetic, one rounding to bf16 on
+ * top of each branch's own); no branch is stored in full and there is no blend pass.  The
+ * workspace is that of a layer whose heads all take route 2.  fp32: three full outputs in the
+ * workspace and a blend pass. */
 int vorta_soft_mixture_workspace_bytes(const vorta_plan* plan, size_t* bytes);
 int vorta_soft_mixture_layer(vorta_plan* plan, const void* q, const void* k, const void* v,
                              const float* alpha_host, void* out, void* workspace,

@@ -21,7 +21,9 @@ check them):
     divide an axis, the last tile of that axis is clipped to the grid.
   * get_window_center_id clamps the query tile id so the window stays inside
     the tile grid (mode "clamp", the sliding-*tile* behaviour); mode
-    "identity" leaves it unchanged (windows truncated at the border).
+    "identity" leaves it unchanged (windows truncated at the border); mode
+    "block" gives every query tile of a block of w tiles the block's middle
+    tile (the 3-D form of section 3.2's tau(i)).
   * similarity = cosine between the bucket's centre token and each other token
     of the bucket, on a caller-chosen feature (the head's keys by default).
   * centre = token at local coordinate floor(b'/2) per axis of the (possibly
@@ -89,12 +91,25 @@ def tile_grid(grid, tile) -> Tuple[int, int, int]:
     return tuple(-(-g // t) for g, t in zip(grid, tile))
 
 
+CENTER_MODES = ("clamp", "identity", "block")
+
+
 def get_window_center_id(q, n_tiles, window, mode: str = "clamp"):
-    """Tile id the window of query tile q is centred on."""
+    """Tile id the window of query tile q is centred on (Algorithm 1 names the function and
+    says only that all queries of one window share the centre's tile id).  Three readings:
+      clamp     the query tile's id, moved inward so that the window stays inside the tile grid
+                (the sliding-tile behaviour section 3.2 adopts); the default
+      identity  the query tile's own id (windows cut off at the border)
+      block     the tile grid is cut into blocks of w tiles per axis and every query tile of a
+                block shares the block's middle tile, floor(q / w) w + floor(w / 2) -- the 3-D
+                form of section 3.2's tau(i); the centre of a partial last block may lie past
+                the grid, which only means fewer of its key tiles exist."""
+    if mode not in CENTER_MODES:
+        raise ValueError(mode)
     if mode == "identity":
         return tuple(q)
-    if mode != "clamp":
-        raise ValueError(mode)
+    if mode == "block":
+        return tuple((qd // wd) * wd + wd // 2 for qd, wd in zip(q, window))
     out = []
     for qd, nd, wd in zip(q, n_tiles, window):
         half = wd // 2
@@ -103,37 +118,53 @@ def get_window_center_id(q, n_tiles, window, mode: str = "clamp"):
     return tuple(out)
 
 
-def sta_mask_entry(i: int, j: int, grid, tile, window, mode: str = "clamp") -> bool:
-    """One entry M[i, j] of Algorithm 1, exactly as its loop body states it."""
-    n_tiles = tile_grid(grid, tile)
-    q = get_tile_id_3d(i, grid, tile)
-    k = get_tile_id_3d(j, grid, tile)
-    q = get_window_center_id(q, n_tiles, window, mode)
-    m = abs(q[0] - k[0]) <= window[0] / 2
-    m = m and abs(q[1] - k[1]) <= window[1] / 2
-    m = m and abs(q[2] - k[2]) <= window[2] / 2
-    return bool(m)
+def axis_tile_ids(grid, tile):
+    """Per axis, the tile id of every token of the flattened grid: three int arrays of length L."""
+    F, H, W = grid
+    i = np.arange(F * H * W)
+    return ((i // (H * W)) // tile[0], ((i // W) % H) // tile[1], (i % W) // tile[2])
 
 
-def sta_mask_dense(grid, tile, window, mode: str = "clamp") -> np.ndarray:
-    """The whole L x L mask by Algorithm 1's double loop.  Tiny grids only."""
-    L = grid[0] * grid[1] * grid[2]
-    M = np.zeros((L, L), dtype=bool)
-    for i in range(L):
-        for j in range(L):
-            M[i, j] = sta_mask_entry(i, j, grid, tile, window, mode)
-    return M
+def visible_key_tiles(centre, n_tiles, window):
+    """Algorithm 1's test per axis: key tile k of axis a is visible from a window centred on
+    centre[a] when abs(centre[a] - k) <= window[a] / 2.  Returns three boolean vectors over the
+    tile ids of each axis; a key tile is visible when all three of its coordinates are."""
+    return tuple(np.abs(c - np.arange(n)) <= w / 2 for c, n, w in zip(centre, n_tiles, window))
 
 
 def sta_mask_row(i: int, grid, tile, window, mode: str = "clamp") -> np.ndarray:
-    """Row i of the mask, the same test evaluated for all j at once."""
-    F, H, W = grid
+    """Row i of Algorithm 1's mask M: the keys whose tile is visible from query i's window."""
     n_tiles = tile_grid(grid, tile)
-    c = get_window_center_id(get_tile_id_3d(i, grid, tile), n_tiles, window, mode)
-    j = np.arange(F * H * W)
-    kf, kh, kw = (j // (H * W)) // tile[0], ((j // W) % H) // tile[1], (j % W) // tile[2]
-    return ((np.abs(c[0] - kf) <= window[0] / 2) & (np.abs(c[1] - kh) <= window[1] / 2)
-            & (np.abs(c[2] - kw) <= window[2] / 2))
+    centre = get_window_center_id(get_tile_id_3d(i, grid, tile), n_tiles, window, mode)
+    vis = visible_key_tiles(centre, n_tiles, window)
+    kf, kh, kw = axis_tile_ids(grid, tile)
+    return vis[0][kf] & vis[1][kh] & vis[2][kw]
+
+
+def sta_mask_entry(i: int, j: int, grid, tile, window, mode: str = "clamp") -> bool:
+    """One entry M[i, j]: is key j's tile inside the window of query i?"""
+    n_tiles = tile_grid(grid, tile)
+    centre = get_window_center_id(get_tile_id_3d(i, grid, tile), n_tiles, window, mode)
+    key_tile = get_tile_id_3d(j, grid, tile)
+    return all(abs(c - k) <= w / 2 for c, k, w in zip(centre, key_tile, window))
+
+
+def sta_mask_dense(grid, tile, window, mode: str = "clamp") -> np.ndarray:
+    """The whole L x L mask, built tile block by tile block: the mask is constant over
+    (query tile) x (key tile) blocks, so each query tile's visible key tiles are expanded to
+    tokens once.  Tiny grids only."""
+    n_tiles = tile_grid(grid, tile)
+    kf, kh, kw = axis_tile_ids(grid, tile)
+    L = len(kf)
+    M = np.zeros((L, L), dtype=bool)
+    for qf in range(n_tiles[0]):
+        for qh in range(n_tiles[1]):
+            for qw in range(n_tiles[2]):
+                centre = get_window_center_id((qf, qh, qw), n_tiles, window, mode)
+                vis = visible_key_tiles(centre, n_tiles, window)
+                queries = (kf == qf) & (kh == qh) & (kw == qw)
+                M[np.ix_(queries, vis[0][kf] & vis[1][kh] & vis[2][kw])] = True
+    return M
 
 
 # --------------------------------------------------------------------------

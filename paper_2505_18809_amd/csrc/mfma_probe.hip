@@ -1,4 +1,5 @@
-// Measurement aid, not part of the attention path: the matrix-pipe rate this chip sustains for
+// Measurement aid, built into a library of its own (libvorta_probe.so) that only the benchmark
+// loads; not part of the attention path or of libvorta's ABI: the matrix-pipe rate this chip sustains for
 // v_mfma_f32_32x32x16_bf16 when nothing else runs, as a function of the operand data.  The
 // nominal peak (256 CUs x 4 SIMDs x one 32x32x16 instruction per 32 cycles x 2.4 GHz) assumes
 // the nominal clock; under sustained matrix load the clock is set by power, and the power of a
@@ -6,7 +7,7 @@
 // against the nominal peak; this probe says how much of it random bf16 data can reach at all.
 #include <hip/hip_runtime.h>
 
-#include "vorta_internal.h"
+#include <cstdint>
 
 namespace vorta {
 
@@ -49,14 +50,17 @@ __global__ __launch_bounds__(512, 1) void mfma_rate_kernel(const uint4* __restri
 
 }  // namespace vorta
 
-extern "C" int vorta_probe_mfma_rate(const void* operands, int32_t iters, int32_t workgroups, void* sink,
-                                     void* clocks, void* stream) {
+// Runs only v_mfma_f32_32x32x16_bf16 (8 wavefronts per workgroup, `workgroups` workgroups,
+// `iters` x 32 instructions per wavefront) on the operand bits the caller supplies.  operands:
+// device, 16 x 64 x 16 bytes (8 A and 8 B fragments per lane); sink: device float[workgroups * 512];
+// clocks: device int64[2], receives shader-clock ticks and 100 MHz ticks of workgroup 0.
+// FLOPs = workgroups * 8 * iters * 32 * 32768.  Returns 0, -1 (bad argument) or the hipError_t
+// of the launch.
+extern "C" int mfma_probe_rate(const void* operands, int32_t iters, int32_t workgroups, void* sink, void* clocks,
+                               void* stream) {
   using namespace vorta;
-  clear_error();
-  if (!operands || !sink || !clocks || iters < 1 || workgroups < 1) return fail(VORTA_EINVAL, "bad probe arguments");
+  if (!operands || !sink || !clocks || iters < 1 || workgroups < 1) return -1;
   hipLaunchKernelGGL(mfma_rate_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)stream, (const uint4*)operands,
                      iters, (float*)sink, (long long*)clocks);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(VORTA_EHIP, "launch of mfma_rate_kernel: %s", hipGetErrorString(e));
-  return VORTA_OK;
+  return (int)hipGetLastError();
 }

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <mutex>
 
 #include "vorta_attn_common.h"
 
@@ -113,7 +114,7 @@ static int layer(vorta_plan* p, const RouteLists& rl, const void* q, const void*
     VORTA_TRY(launch_reorder(p, rl, v, c.buf[2], true, stream));
   }
   // route 2: core-set index on K, then pool Q, K, V
-  VORTA_TRY(launch_bcs_index(p, rl, k, keep_idx, assign, stream));
+  VORTA_TRY(launch_bcs_index(p, rl, user_tensor(p, k), keep_idx, assign, stream));
   VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, c.buf[4], stream));
   VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, c.buf[5], stream));
   VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, c.buf[6], stream));
@@ -154,15 +155,25 @@ int vorta_reorder_from_tiles(vorta_plan* p, const void* src, const uint8_t* rout
   return launch_reorder(p, rl, dst, const_cast<void*>(src), false, stream);
 }
 
-int vorta_bcs_build_index(vorta_plan* p, const void* feat, const uint8_t* routes, int32_t* keep_idx,
-                          int32_t* assign, void* stream) {
+int vorta_bcs_build_index(vorta_plan* p, const void* feat, int64_t feat_head_stride, const uint8_t* routes,
+                          int32_t* keep_idx, int32_t* assign, void* stream) {
   RouteLists rl;
   VORTA_TRY(begin(p, routes, &rl));
+  if (feat_head_stride < VORTA_FEAT_USER_LAYOUT)
+    return fail(VORTA_EINVAL, "feat_head_stride = %lld: VORTA_FEAT_USER_LAYOUT, 0 or a positive stride", (long long)feat_head_stride);
+  if (feat_head_stride > 0 && (feat_head_stride < p->L * p->d.head_dim || feat_head_stride % (16 / p->elem_bytes)))
+    return fail(VORTA_EINVAL, "feat_head_stride = %lld: heads overlap (a head holds %lld elements) or lose 16-byte alignment",
+                (long long)feat_head_stride, (long long)(p->L * p->d.head_dim));
   if (!rl.count[2]) return VORTA_OK;
   VORTA_TRY(check_ptr(feat, "feat"));
   VORTA_TRY(check_ptr(keep_idx, "keep_idx"));
   VORTA_TRY(check_ptr(assign, "assign"));
-  return launch_bcs_index(p, rl, feat, keep_idx, assign, stream);
+  UserTensor ut = user_tensor(p, feat);
+  if (feat_head_stride != VORTA_FEAT_USER_LAYOUT) {   // [heads or 1][rows][head_dim]
+    ut.head_stride = feat_head_stride;
+    ut.row_stride = p->d.head_dim;
+  }
+  return launch_bcs_index(p, rl, ut, keep_idx, assign, stream);
 }
 
 int vorta_bcs_pool(vorta_plan* p, const void* src, const uint8_t* routes, const int32_t* keep_idx,
@@ -188,6 +199,8 @@ int vorta_scatter_back(vorta_plan* p, const uint8_t* routes, const void* o_t, co
   RouteLists rl;
   VORTA_TRY(begin(p, routes, &rl));
   if (rl.count[1] || rl.count[2]) VORTA_TRY(check_ptr(out, "out"));
+  if (rl.count[1] && !o_t && p->d.dtype != VORTA_BF16)
+    return fail(VORTA_EINVAL, "o_t is null: only the bf16 window kernel writes its rows to `out` itself");
   if (rl.count[1] && o_t) {      // o_t null: the window heads wrote their rows to `out` themselves
     VORTA_TRY(check_ptr(o_t, "o_t"));
     VORTA_TRY(launch_reorder(p, rl, out, const_cast<void*>(o_t), false, stream));
@@ -223,11 +236,49 @@ int vorta_soft_mixture_layer(vorta_plan* p, const void* q, const void* k, const 
   VORTA_TRY(vorta_soft_mixture_workspace_bytes(p, &need));
   if (workspace_bytes < need) return fail(VORTA_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, need);
   VORTA_TRY(check_ptr(workspace, "workspace"));
+  uint8_t routes[VORTA_MAX_HEADS];
+  if (p->d.dtype == VORTA_BF16) {
+    // Fused form: no branch is written out in full and there is no blend pass.
+    //   1. core-set branch of every head -> o_c (pooled rows only)
+    //   2. sliding-tile branch of every head -> the video rows of `out`, unscaled
+    //   3. full-attention branch of every head; its epilogue reads the row `out` holds and the
+    //      row of o_c the token is assigned to, and writes a1 full + a2 sliding + a3 core-set.
+    // The three run in this order on the stream, so each finds its inputs complete.
+    RouteLists rl;
+    Carved c;
+    std::memset(routes, VORTA_ROUTE_CORESET, sizeof(routes));
+    VORTA_TRY(begin(p, routes, &rl));
+    VORTA_TRY(carve(p, routes, workspace, workspace_bytes, &c));
+    int32_t* keep_idx = (int32_t*)c.buf[8];
+    int32_t* assign = (int32_t*)c.buf[9];
+    VORTA_TRY(launch_bcs_index(p, rl, user_tensor(p, k), keep_idx, assign, stream));
+    VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, c.buf[4], stream));
+    VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, c.buf[5], stream));
+    VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, c.buf[6], stream));
+    vorta_attn_io io;
+    std::memset(&io, 0, sizeof(io));
+    io.q = q; io.k = k; io.v = v; io.out = out;
+    io.q_c = c.buf[4]; io.k_c = c.buf[5]; io.v_c = c.buf[6]; io.o_c = c.buf[7];
+    VORTA_TRY(launch_attention_bf16(p, rl, &io, stream));
+    std::memset(routes, VORTA_ROUTE_WINDOW, sizeof(routes));
+    VORTA_TRY(split_routes(p, routes, &rl));
+    VORTA_TRY(launch_attention_bf16(p, rl, &io, stream, nullptr, false));
+    std::memset(routes, VORTA_ROUTE_FULL, sizeof(routes));
+    VORTA_TRY(split_routes(p, routes, &rl));
+    MixArgs mix;
+    std::memset(&mix, 0, sizeof(mix));
+    mix.oc = c.buf[7];
+    mix.assign = assign;
+    mix.Lc = (int)p->Lc;
+    for (int h = 0; h < p->d.heads; ++h)
+      for (int r = 0; r < 3; ++r) mix.alpha[h][r] = alpha_host[3 * h + r];
+    return launch_attention_bf16(p, rl, &io, stream, &mix);
+  }
+  // fp32 (the exact path): every branch into a buffer of its own, then one blend pass
   const size_t out_bytes = ((size_t)p->d.heads * p->N * p->d.head_dim * p->elem_bytes + 255) & ~(size_t)255;
   char* branch[3] = {(char*)workspace, (char*)workspace + out_bytes, (char*)workspace + 2 * out_bytes};
   char* inner = (char*)workspace + 3 * out_bytes;
   const size_t inner_bytes = workspace_bytes - 3 * out_bytes;
-  uint8_t routes[VORTA_MAX_HEADS];
   for (int r = 0; r < 3; ++r) {
     std::memset(routes, r, sizeof(routes));
     RouteLists rl;
@@ -237,6 +288,27 @@ int vorta_soft_mixture_layer(vorta_plan* p, const void* q, const void* k, const 
     VORTA_TRY(layer(p, rl, q, k, v, routes, branch[r], c, stream));
   }
   return launch_blend3(p, branch[0], branch[1], branch[2], alpha_host, out, stream);
+}
+
+int vorta_plan_upload(vorta_plan* p) {
+  clear_error();
+  if (!p) return fail(VORTA_EINVAL, "null plan");
+  return ensure_device_tables(p);
+}
+
+int vorta_router_device(const float* t_emb, const float* w_r, int32_t n_steps, int32_t d_t, int32_t heads,
+                        float* alpha, uint8_t* routes, uint8_t* routes_host, void* stream) {
+  clear_error();
+  if (n_steps < 1 || d_t < 1 || heads < 1 || heads > VORTA_MAX_HEADS || n_steps > 65535)
+    return fail(VORTA_EINVAL, "n_steps = %d (1..65535), d_t = %d (>= 1), heads = %d (1..%d)", n_steps, d_t, heads, VORTA_MAX_HEADS);
+  if (!t_emb || !w_r || !alpha || !routes) return fail(VORTA_EINVAL, "null argument");
+  if (((uintptr_t)t_emb | (uintptr_t)w_r | (uintptr_t)alpha) & 3) return fail(VORTA_EALIGN, "float arrays must be 4-byte aligned");
+  VORTA_TRY(launch_router(t_emb, w_r, n_steps, d_t, heads, alpha, routes, stream));
+  if (routes_host) {
+    hipError_t e = hipMemcpyAsync(routes_host, routes, (size_t)n_steps * heads, hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(VORTA_EHIP, "copy of the routes to the host: %s", hipGetErrorString(e));
+  }
+  return VORTA_OK;
 }
 
 }  // extern "C"

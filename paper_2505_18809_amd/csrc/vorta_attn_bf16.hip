@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "vorta_attn_common.h"
 
@@ -462,8 +463,14 @@ __device__ __forceinline__ float elem_of(const f32x16& t0, const f32x16& t1, int
 // NWV: wavefronts per workgroup.  8: 256 query rows, 64-key blocks, one workgroup per CU (dense,
 // core-set, window tiles of more than 128 tokens).  4: 128 query rows, 32-key blocks, half the
 // ring, two workgroups per CU (smaller window tiles): the iteration has 16 slots instead of 32.
-template <bool WIN, int NWV>
-__global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const AttnArgs a) {
+// MIX: the launch is the last of the three branches of Eq. 5 (dense items over every head) and
+// its epilogue writes the gate-weighted sum of the three (see MixArgs).
+template <bool WIN, int NWV, bool MIX = false>
+__global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const AttnArgs a,
+                                                                            const std::conditional_t<MIX, MixArgs, NoMix> mx) {
+  static_assert(!(MIX && WIN), "the Eq. 5 epilogue belongs to the dense launch");
+  static_assert(pipe_lds_bytes(NWV) <= 160 * 1024, "K and V rings exceed the 160 KB of LDS of a CU");
+  static_assert(32 * NWV * LSTR * 2 <= pipe_lds_bytes(NWV), "output staging does not fit in the rings it reuses");
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   constexpr int KB = 8 * NWV;               // keys per block: 64 (8 wavefronts) or 32 (4)
   constexpr int NS = KB / 2;                // slots = matrix instructions per iteration
@@ -544,7 +551,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   const unsigned lds0 = (unsigned)(uintptr_t)(lds_ptr)smem;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   auto dma16 = [&](const i32x4& rs, unsigned lds_addr, unsigned off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(off * 2u), "s"(rs) : "memory", "m0");
+    asm volatile("s_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"{m0}"(lds_addr), "v"(off * 2u), "s"(rs) : "memory");
   };
   // group wave + NWV h of K / V block b (h = 0, 1: this lane's first and second staging row)
   auto dma_k = [&](int h, int b, unsigned off) { dma16(rs_k, lds0 + 2u * (unsigned)((b & 3) * K_STAGE + (wave_u + NWV * h) * KG), off); };
@@ -864,8 +871,30 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int row = (lane >> 4) + 4 * i;
-    if (32 * wave + row < w.n_rows)
-      *(uint4*)(O + orow[i] * row_stride + (lane & 15) * 8) = *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+    if (32 * wave + row < w.n_rows) {
+      uint4 mine = *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
+      uint4* dst = (uint4*)(O + orow[i] * row_stride + (lane & 15) * 8);
+      if constexpr (MIX) {
+        const int tok = (int)orow[i];
+        const bool video = tok < a.L;
+        const int slot = video ? mx.assign[(long)w.head * a.L + tok] : mx.Lc + (tok - a.L);
+        const uint4 core = *(const uint4*)((const uint16_t*)mx.oc + ((long)w.head * a.Nc + slot) * D + (lane & 15) * 8);
+        const uint4 slide = video ? *dst : mine;
+        const float a1 = mx.alpha[w.head][0], a2 = mx.alpha[w.head][1], a3 = mx.alpha[w.head][2];
+        const unsigned f[4] = {mine.x, mine.y, mine.z, mine.w}, s2[4] = {slide.x, slide.y, slide.z, slide.w},
+                       c3[4] = {core.x, core.y, core.z, core.w};
+        unsigned r[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = a1 * __uint_as_float(f[e] << 16) + a2 * __uint_as_float(s2[e] << 16) + a3 * __uint_as_float(c3[e] << 16);
+          const float hi = a1 * __uint_as_float(f[e] & 0xffff0000u) + a2 * __uint_as_float(s2[e] & 0xffff0000u) +
+                           a3 * __uint_as_float(c3[e] & 0xffff0000u);
+          r[e] = pack_bf16(lo, hi);
+        }
+        mine = make_uint4(r[0], r[1], r[2], r[3]);
+      }
+      *dst = mine;
+    }
   }
 }
 
@@ -875,27 +904,36 @@ static int set_lds_limit(const void* kernel, const char* name, int bytes) {
   return VORTA_OK;
 }
 
-int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream) {
+// mix: the launch is the full-attention branch of Eq. 5 over the heads of route 0 and blends the
+// other two branches in (their results must be complete on the stream).  win_text = false leaves
+// out the text rows of the window heads (under Eq. 5 they equal the full-attention branch's).
+int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream,
+                          const MixArgs* mix, bool win_text) {
   static std::once_flag once;
   static int attr_rc = VORTA_OK;
   std::call_once(once, [] {
     attr_rc = set_lds_limit((const void*)attn_bf16_kernel<4>, "attn_bf16_kernel<4>", LDS_BYTES);
     if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<false, 8>, "attn_bf16_pipe_kernel<false, 8>", pipe_lds_bytes(8));
+    if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<false, 8, true>, "attn_bf16_pipe_kernel<false, 8, true>", pipe_lds_bytes(8));
     if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true, 8>, "attn_bf16_pipe_kernel<true, 8>", pipe_lds_bytes(8));
     if (!attr_rc) attr_rc = set_lds_limit((const void*)attn_bf16_pipe_kernel<true, 4>, "attn_bf16_pipe_kernel<true, 4>", pipe_lds_bytes(4));
   });
   if (attr_rc) return attr_rc;
+  if (mix && (rl.count[1] || rl.count[2])) return fail(VORTA_EINVAL, "the Eq. 5 epilogue takes full-attention heads only");
   // Long items -- dense heads, core-set heads and the text rows of the window heads, which
   // attend to every row -- run on the pipelined kernel in 256-row workgroups.
   RouteLists win_rl = rl;
   win_rl.count[0] = win_rl.count[2] = 0;
   AttnArgs a;
-  if (int rc = fill_attn_args(p, rl, io, BM_LONG, WIN_TEXT, &a)) return rc;
+  if (int rc = fill_attn_args(p, rl, io, BM_LONG, win_text ? WIN_TEXT : WIN_NONE, &a)) return rc;
   if (a.end_tile > 0) {
     // the last items (at most one per two CUs) go out as half-row items: see AttnArgs::split_from
     const int n_split = std::min(a.end_tile, p->n_cus / 2);
     a.split_from = a.end_tile - n_split;
-    hipLaunchKernelGGL((attn_bf16_pipe_kernel<false, 8>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a);
+    if (mix)
+      hipLaunchKernelGGL((attn_bf16_pipe_kernel<false, 8, true>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a, *mix);
+    else
+      hipLaunchKernelGGL((attn_bf16_pipe_kernel<false, 8>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a, NoMix());
   }
   // Window tiles.  Gathered from the caller's tensors (no tile-ordered copies given): the
   // pipelined kernel again -- tiles of more than 128 tokens in 256-row workgroups of 8
@@ -906,9 +944,9 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   if (a.end_tile > 0 && win_long) {
     const int n_split = std::min(a.end_tile, p->n_cus / 2);
     a.split_from = a.end_tile - n_split;
-    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 8>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a);
+    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 8>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a, NoMix());
   } else if (a.end_tile > 0 && a.win_gather) {
-    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 4>), dim3(a.end_tile), dim3(256), pipe_lds_bytes(4), (hipStream_t)stream, a);
+    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 4>), dim3(a.end_tile), dim3(256), pipe_lds_bytes(4), (hipStream_t)stream, a, NoMix());
   } else if (a.end_tile > 0) {
     hipLaunchKernelGGL((attn_bf16_kernel<4>), dim3(a.end_tile), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
   }

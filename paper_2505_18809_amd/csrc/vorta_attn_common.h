@@ -51,9 +51,23 @@ struct AttnArgs {
   uint8_t win_heads[VORTA_MAX_HEADS];
 };
 
+// Eq. 5 epilogue of a dense launch over all heads: the rows it writes are
+//   a1 (its own result) + a2 (the sliding-tile result, already in `out`) + a3 (core-set result of
+//   the slot the row is assigned to),
+// the first still in registers / LDS, the other two read as bf16 rows.  Text rows see every key
+// under the sliding-tile branch too, so for them the second term equals the first.
+struct MixArgs {
+  const void* oc;              // [heads][Nc][d]: core-set outputs of every head
+  const int* assign;           // [heads][L]
+  int Lc;
+  float alpha[VORTA_MAX_HEADS][3];
+};
+struct NoMix {};
+
 struct WorkItem {
   long q_off, kv_off, o_off;   // element offsets of the head's row 0 in q / k,v / o
   long row_stride;             // elements
+  int head;                    // head id (dense segment only)
   int seg;                     // 0 dense, 1 core-set, 2 window
   int row0, n_rows;            // query rows [row0, row0 + n_rows)
   int n_runs;
@@ -66,6 +80,7 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
   WorkItem w;
   w.runs = nullptr;
   w.n_runs = 1;
+  w.head = 0;
   int half = -1;
   if (item >= a.split_from) {
     half = (item - a.split_from) & 1;
@@ -83,6 +98,7 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
     item -= a.end_text;
     const int slot = item / a.qb_dense, qb = item - slot * a.qb_dense;
     w.seg = 0;
+    w.head = a.dense_heads[slot];
     w.q_off = w.kv_off = w.o_off = a.dense_heads[slot] * a.head_stride0;
     w.row_stride = a.row_stride0;
     w.row0 = qb * BM;
@@ -137,5 +153,8 @@ enum WindowPart { WIN_NONE = 0, WIN_TEXT = 1, WIN_TILES = 2, WIN_ALL = 3 };
 // Fills AttnArgs for a launch over the heads of rl with BM-row work items; win_part selects
 // which items of the window heads it carries.
 int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, int win_part, AttnArgs* a);
+
+int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream,
+                          const MixArgs* mix = nullptr, bool win_text = true);
 
 }  // namespace vorta

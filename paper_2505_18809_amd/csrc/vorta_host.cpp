@@ -23,6 +23,8 @@ int fail(int code, const char* fmt, ...) {
 
 void clear_error() { g_err[0] = 0; }
 
+void (*g_release_device_tables)(vorta_plan* p) = nullptr;
+
 int split_routes(const vorta_plan* p, const uint8_t* routes, RouteLists* out) {
   if (!p || !routes || !out) return fail(VORTA_EINVAL, "null plan or routes");
   *out = RouteLists();
@@ -71,9 +73,12 @@ const char* vorta_strerror(int code) {
 const char* vorta_last_error(void) { return g_err; }
 
 // Window centre of Algorithm 1's get_window_center_id: "clamp" keeps the window inside the
-// tile grid, "identity" leaves the query tile as the centre.
+// tile grid, "identity" leaves the query tile as the centre, "block" gives every query tile of a
+// block of w tiles the block's middle tile (section 3.2's tau(i) per axis; the centre of a
+// partial last block may lie past the grid).
 static int window_centre(int q, int n, int w, int mode) {
   if (mode == VORTA_CENTER_IDENTITY) return q;
+  if (mode == VORTA_CENTER_BLOCK) return q - q % w + w / 2;
   const int half = w / 2;
   const int lo = half, hi = std::max(n - 1 - half, half);
   return std::min(std::max(q, lo), hi);
@@ -83,11 +88,19 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
   clear_error();
   if (!desc || !out) return fail(VORTA_EINVAL, "null desc or out");
   *out = nullptr;
-  const vorta_layer_desc& d = *desc;
+  vorta_layer_desc d = *desc;
   if (d.F < 1 || d.H < 1 || d.W < 1 || d.n_text < 0)
     return fail(VORTA_ESHAPE, "grid %dx%dx%d / n_text %d must be positive", d.F, d.H, d.W, d.n_text);
-  if ((int64_t)d.F * d.H * d.W + d.n_text > (int64_t)1 << 30)
-    return fail(VORTA_ESHAPE, "more than 2^30 tokens");
+  {
+    // axis by axis, so that no product leaves the range of int64
+    const int64_t cap = (int64_t)1 << 30;
+    int64_t tokens = d.F;
+    for (int64_t axis : {(int64_t)d.H, (int64_t)d.W}) {
+      if (tokens > cap || axis > cap) return fail(VORTA_ESHAPE, "more than 2^30 tokens");
+      tokens *= axis;
+    }
+    if (tokens + d.n_text > cap) return fail(VORTA_ESHAPE, "more than 2^30 tokens");
+  }
   if (d.heads < 1 || d.heads > VORTA_MAX_HEADS)
     return fail(VORTA_ESHAPE, "heads = %d, supported 1..%d", d.heads, VORTA_MAX_HEADS);
   if (d.dtype != VORTA_F32 && d.dtype != VORTA_BF16) return fail(VORTA_EDTYPE, "dtype %d", d.dtype);
@@ -97,15 +110,24 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
     return fail(VORTA_ESHAPE, "fp32 supports head_dim 64 or 128, got %d", d.head_dim);
   if (d.layout != VORTA_LAYOUT_NHD && d.layout != VORTA_LAYOUT_HND)
     return fail(VORTA_EINVAL, "layout %d", d.layout);
-  if (d.center_mode != VORTA_CENTER_CLAMP && d.center_mode != VORTA_CENTER_IDENTITY)
+  if (d.center_mode != VORTA_CENTER_CLAMP && d.center_mode != VORTA_CENTER_IDENTITY &&
+      d.center_mode != VORTA_CENTER_BLOCK)
     return fail(VORTA_EINVAL, "center_mode %d", d.center_mode);
   const int grid[3] = {d.F, d.H, d.W};
-  int64_t bucket_tokens = 1;
+  int64_t bucket_tokens = 1, tile_tokens = 1;
   for (int a = 0; a < 3; ++a) {
     if (d.tile[a] < 1) return fail(VORTA_ESHAPE, "tile[%d] = %d < 1", a, d.tile[a]);
     if (d.window[a] < 1) return fail(VORTA_ESHAPE, "window[%d] = %d < 1", a, d.window[a]);
     if (d.bucket[a] < 1) return fail(VORTA_ESHAPE, "bucket[%d] = %d < 1", a, d.bucket[a]);
+    // A tile or bucket larger than the axis is one clipped tile / bucket; a window of 2 n + 1
+    // tiles or more sees the whole axis under every centre rule.  From here on the plan works
+    // with the clipped values, so no product or sum below can leave the range of the grid.
+    d.tile[a] = std::min(d.tile[a], grid[a]);
+    d.bucket[a] = std::min(d.bucket[a], grid[a]);
+    const int n_axis = (grid[a] + d.tile[a] - 1) / d.tile[a];
+    d.window[a] = (int)std::min<int64_t>(d.window[a], 2 * (int64_t)n_axis + 1);
     bucket_tokens *= d.bucket[a];
+    tile_tokens *= d.tile[a];
   }
   if (bucket_tokens > 64) return fail(VORTA_ESHAPE, "bucket holds %lld tokens, at most 64", (long long)bucket_tokens);
   if (d.keep_num < 1 || d.keep_den < d.keep_num)
@@ -126,7 +148,7 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
   p->N = p->L + d.n_text;
   p->elem_bytes = d.dtype == VORTA_BF16 ? 2 : 4;
   p->scale = d.softmax_scale > 0.f ? d.softmax_scale : (float)(1.0 / std::sqrt((double)d.head_dim));
-  p->tile_tokens = d.tile[0] * d.tile[1] * d.tile[2];
+  p->tile_tokens = (int)tile_tokens;   // <= L <= 2^30: every tile extent is clipped to its axis
   for (int a = 0; a < 3; ++a) {
     p->nt[a] = (grid[a] + d.tile[a] - 1) / d.tile[a];   // the last tile of an axis is clipped to the grid
     p->nb[a] = (grid[a] + d.bucket[a] - 1) / d.bucket[a];
@@ -215,6 +237,14 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
   p->slot_base[b] = (int32_t)slot;
   p->Lc = slot;
   *out = p;
+  return VORTA_OK;
+}
+
+int vorta_plan_destroy(vorta_plan* p) {
+  clear_error();
+  if (!p) return VORTA_OK;
+  if (p->on_device && g_release_device_tables) g_release_device_tables(p);
+  delete p;
   return VORTA_OK;
 }
 
@@ -367,9 +397,14 @@ int vorta_workspace_bytes(const vorta_plan* p, const uint8_t* routes_host, size_
 int vorta_soft_mixture_workspace_bytes(const vorta_plan* p, size_t* bytes) {
   clear_error();
   if (!p || !bytes) return fail(VORTA_EINVAL, "null argument");
-  // the largest single-route workspace + two extra user-layout outputs
-  size_t most = 0;
   uint8_t routes[VORTA_MAX_HEADS];
+  if (p->d.dtype == VORTA_BF16) {
+    // fused form: the core-set buffers and index of every head, nothing else
+    std::memset(routes, VORTA_ROUTE_CORESET, sizeof(routes));
+    return vorta_workspace_bytes(p, routes, bytes);
+  }
+  // fp32: the largest single-route workspace + one user-layout output per branch
+  size_t most = 0;
   for (int r = 0; r < 3; ++r) {
     std::memset(routes, r, sizeof(routes));
     size_t b = 0;

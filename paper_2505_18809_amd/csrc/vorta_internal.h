@@ -51,7 +51,9 @@ struct RouteLists {
 };
 int split_routes(const vorta_plan* p, const uint8_t* routes, RouteLists* out);
 
-int ensure_device_tables(vorta_plan* p);         // vorta_device.hip
+int ensure_device_tables(vorta_plan* p);         // vorta_passes.hip
+// set by the device side when it is linked in: frees the device tables of a plan
+extern void (*g_release_device_tables)(vorta_plan* p);
 
 // Launchers (each returns VORTA_OK / VORTA_EHIP).  Pointers are device memory.
 struct UserTensor {                               // a tensor in the caller's layout
@@ -63,14 +65,16 @@ UserTensor user_tensor(const vorta_plan* p, const void* base);
 
 int launch_reorder(vorta_plan* p, const RouteLists& rl, const void* user, void* tiled, bool to_tiles,
                    void* stream);
-int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const void* feat, int32_t* keep_idx,
+// feat.head_stride == 0: one feature tensor shared by every head
+int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const UserTensor& feat, int32_t* keep_idx,
                      int32_t* assign, void* stream);
 int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const int32_t* keep_idx,
                     const int32_t* assign, void* dst, void* stream);
 int launch_unpool(vorta_plan* p, const RouteLists& rl, const void* o_c, const int32_t* assign, void* out,
                   void* stream);
-int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream);
 int launch_attention_f32(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream);
+int launch_router(const float* t_emb, const float* w_r, int n_steps, int d_t, int heads, float* alpha,
+                  uint8_t* routes, void* stream);
 int launch_blend3(vorta_plan* p, const void* o0, const void* o1, const void* o2, const float* alpha_host,
                   void* out, void* stream);
 

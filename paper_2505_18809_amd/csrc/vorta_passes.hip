@@ -39,6 +39,8 @@ static void release_device_tables(vorta_plan* p) {
     *t = nullptr;
   }
 }
+// vorta_plan_destroy lives with the host code; it frees the device tables through this hook
+static const bool release_hook_set = (g_release_device_tables = release_device_tables, true);
 
 static int upload_device_tables(vorta_plan* p, int dev) {
   if (int rc = upload_table(p->runs, &p->d_runs)) return rc;
@@ -342,10 +344,10 @@ __global__ __launch_bounds__(256) void bcs_index_kernel(const T* __restrict__ fe
   }
 }
 
-int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const void* feat, int32_t* keep_idx,
+int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const UserTensor& ut, int32_t* keep_idx,
                      int32_t* assign, void* stream) {
   if (rl.count[2] == 0) return VORTA_OK;
-  const UserTensor ut = user_tensor(p, feat);
+  const void* feat = ut.base;
   const dim3 grid((p->n_buckets + 3) / 4, rl.count[2]);
   const HeadList hl = head_list(rl, 2);
   const Geo g = make_geo(p);
@@ -473,6 +475,51 @@ int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const 
 }
 
 // ------------------------------------------------------------------------------------------
+// Router (Eq. 3) and hard selection (Eq. 4) for a whole sampling schedule: one wavefront per
+// (step, head).  The gates depend on the timestep embedding only, so every step's routes can be
+// had before sampling starts, in one launch.  The three logits are fp64 sums (lanes stride over
+// d_t, then a fixed xor tree), the softmax is fp64, the gates are stored as fp32; Eq. 4 is
+// decided on the fp64 gates, every tie going to full attention.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void router_kernel(const float* __restrict__ t_emb, const float* __restrict__ w_r,
+                                                    int d_t, int heads, float* __restrict__ alpha,
+                                                    uint8_t* __restrict__ routes) {
+#pragma clang fp contract(off)
+  const int h = blockIdx.x, step = blockIdx.y, lane = threadIdx.x;
+  const float* t = t_emb + (long)step * d_t;
+  const float* w = w_r + (long)h * d_t * 3;
+  double z[3] = {0.0, 0.0, 0.0};
+  for (int i = lane; i < d_t; i += 64) {
+    const double ti = (double)t[i];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) z[k] += ti * (double)w[3 * i + k];
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+    for (int k = 0; k < 3; ++k) z[k] += __shfl_xor(z[k], off, 64);
+  if (lane == 0) {
+    const double m = fmax(z[0], fmax(z[1], z[2]));
+    const double e0 = exp(z[0] - m), e1 = exp(z[1] - m), e2 = exp(z[2] - m);
+    const double sum = e0 + e1 + e2;
+    const double a1 = e0 / sum, a2 = e1 / sum, a3 = e2 / sum;
+    float* out = alpha + ((long)step * heads + h) * 3;
+    out[0] = (float)a1; out[1] = (float)a2; out[2] = (float)a3;
+    uint8_t r = VORTA_ROUTE_FULL;
+    if (a2 > a1 && a2 > a3) r = VORTA_ROUTE_WINDOW;
+    else if (a3 > a1 && a3 > a2) r = VORTA_ROUTE_CORESET;
+    routes[(long)step * heads + h] = r;
+  }
+}
+
+int launch_router(const float* t_emb, const float* w_r, int n_steps, int d_t, int heads, float* alpha,
+                  uint8_t* routes, void* stream) {
+  hipLaunchKernelGGL(router_kernel, dim3(heads, n_steps), dim3(64), 0, (hipStream_t)stream, t_emb, w_r, d_t, heads,
+                     alpha, routes);
+  return launch_status("router_kernel");
+}
+
+// ------------------------------------------------------------------------------------------
 // Eq. 5 blend: out = a1 o_full + a2 o_sliding + a3 o_coreset, gates per head
 // ------------------------------------------------------------------------------------------
 struct Gates {
@@ -513,11 +560,3 @@ int launch_blend3(vorta_plan* p, const void* o0, const void* o1, const void* o2,
 }
 
 }  // namespace vorta
-
-extern "C" int vorta_plan_destroy(vorta_plan* p) {
-  vorta::clear_error();
-  if (!p) return VORTA_OK;
-  if (p->on_device) vorta::release_device_tables(p);
-  delete p;
-  return VORTA_OK;
-}

@@ -64,13 +64,16 @@ def test_tile_permutation_matches_get_tile_id_3d(grid, tile):
         assert (row0 == np.arange(plan.n_tiles + 1) * int(np.prod(tile))).all()
 
 
-@pytest.mark.parametrize("mode", ["clamp", "identity"])
+MODES = {"clamp": 0, "identity": 1, "block": 2}
+
+
+@pytest.mark.parametrize("mode", ["clamp", "identity", "block"])
 @pytest.mark.parametrize("window", [(1, 1, 1), (3, 3, 3), (1, 3, 5), (5, 2, 3)])
 @pytest.mark.parametrize("grid,tile", [((4, 6, 6), (2, 2, 3)), ((5, 7, 6), (2, 3, 4))], ids=["divisible", "clipped"])
 def test_window_boxes_and_runs_expand_to_algorithm_1_mask(window, mode, grid, tile):
     n_text = 5
     plan = vorta.vorta_plan_create(grid, 1, 128, "bf16", tile, window, n_text=n_text,
-                                   center_mode={"clamp": 0, "identity": 1}[mode])
+                                   center_mode=MODES[mode])
     M = vo.sta_mask_dense(grid, tile, window, mode)
     perm = vorta.vorta_tile_permutation(plan)
     inv = np.argsort(perm)
@@ -92,7 +95,7 @@ def test_window_boxes_and_runs_expand_to_algorithm_1_mask(window, mode, grid, ti
         assert (runs[qt, :n_runs[qt], 1] > 0).all()
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(24))
 def test_seeded_random_geometries_expand_to_algorithm_1_mask(seed):
     """Random small grids, tiles (dividing the grid or not), windows and centre rules: the run
     table of every query tile, mapped back through the tile permutation, is exactly the row of
@@ -101,9 +104,9 @@ def test_seeded_random_geometries_expand_to_algorithm_1_mask(seed):
     grid = tuple(int(x) for x in rng.integers(1, 8, 3))
     tile = tuple(int(x) for x in rng.integers(1, 5, 3))
     window = tuple(int(x) for x in rng.choice([1, 2, 3, 5, 7], 3))
-    mode = ["clamp", "identity"][seed % 2]
+    mode = ["clamp", "identity", "block"][seed % 3]
     n_text = int(rng.choice([0, 3]))
-    plan = vorta.vorta_plan_create(grid, 1, 128, "bf16", tile, window, n_text=n_text, center_mode=seed % 2)
+    plan = vorta.vorta_plan_create(grid, 1, 128, "bf16", tile, window, n_text=n_text, center_mode=seed % 3)
     L = plan.n_video
     inv = np.argsort(vorta.vorta_tile_permutation(plan))
     row0 = vorta.vorta_tile_row0(plan)
@@ -119,6 +122,54 @@ def test_seeded_random_geometries_expand_to_algorithm_1_mask(seed):
         assert (np.sort(inv[rows[rows < L]]) == want).all(), (grid, tile, window, mode, i)
         assert sorted(rows[rows >= L]) == list(range(L, L + n_text))
         assert row0[qt] <= np.nonzero(inv == i)[0][0] < row0[qt + 1]
+
+
+def test_block_centres_follow_the_hand_worked_fixture():
+    """The library's run table under VORTA_CENTER_BLOCK against the hand-worked mask in
+    tests/golden (7 tiles, window 3: blocks {0,1,2} {3,4,5} {6})."""
+    from test_oracle_pins import read_mask_fixture
+    want = read_mask_fixture("sta_mask_1x1x14_tile2_win3_block.txt")["block"]
+    plan = vorta.vorta_plan_create((1, 1, 14), 1, 128, "bf16", (1, 1, 2), (1, 1, 3), center_mode=2)
+    boxes = vorta.vorta_window_boxes(plan)
+    assert [tuple(b[4:]) for b in boxes] == [(0, 2)] * 3 + [(3, 5)] * 3 + [(6, 6)]
+    runs, n_runs = vorta.vorta_window_runs(plan)
+    for i in range(14):                                   # one tile row: tile order = raster order
+        got = np.zeros(14, dtype=bool)
+        for s0, c in runs[i // 2, :n_runs[i // 2]]:
+            got[s0:s0 + c] = True
+        assert (got == want[i]).all()
+
+
+@pytest.mark.parametrize("tile,bucket", [((2048, 2048, 2048), (2, 3, 2)), ((70000, 70000, 1), (1000, 1, 1)),
+                                         ((2 ** 31 - 1, 3, 2 ** 31 - 1), (2 ** 31 - 1, 2 ** 31 - 1, 2 ** 31 - 1)),
+                                         ((5, 8, 3), (4, 1, 1))])
+def test_tiles_and_buckets_larger_than_the_grid_are_clipped_to_it(tile, bucket):
+    """A tile (bucket) extent beyond its axis means one tile (bucket) along that axis: the plan
+    must equal the plan made with the extents clipped by hand -- no overflowing products, no
+    zero-sized tiles."""
+    grid = (4, 8, 8)
+    clip = lambda t: tuple(min(x, g) for x, g in zip(t, grid))
+    if int(np.prod(clip(bucket))) > 64:
+        with pytest.raises(vorta.VortaError) as e:
+            vorta.vorta_plan_create(grid, 2, 128, "bf16", tile, (3, 3, 3), bucket=bucket)
+        assert e.value.code == -2
+        bucket = (2, 3, 2)
+    a = vorta.vorta_plan_create(grid, 2, 128, "bf16", tile, (3, 3, 2 ** 31 - 1), bucket=bucket, n_text=3)
+    b = vorta.vorta_plan_create(grid, 2, 128, "bf16", clip(tile), (3, 3, 99), bucket=clip(bucket), n_text=3)
+    assert a.tile_tokens == int(np.prod(clip(tile))) and a.tile_tokens <= a.n_video
+    for name in ("tiles", "n_tiles", "tile_tokens", "window_key_tiles", "max_runs", "n_buckets", "n_core"):
+        assert getattr(a, name) == getattr(b, name), name
+    assert (vorta.vorta_tile_permutation(a) == vorta.vorta_tile_permutation(b)).all()
+    assert (vorta.vorta_tile_row0(a) == vorta.vorta_tile_row0(b)).all()
+    ra, rb = vorta.vorta_window_runs(a), vorta.vorta_window_runs(b)
+    assert (ra[0] == rb[0]).all() and (ra[1] == rb[1]).all()
+    assert (vorta.vorta_bcs_slot_bases(a) == vorta.vorta_bcs_slot_bases(b)).all()
+    perm = vorta.vorta_tile_permutation(a)
+    n = vo.tile_grid(grid, clip(tile))
+    row0 = vorta.vorta_tile_row0(a)
+    for i in range(0, a.n_video, 7):
+        t = int(np.ravel_multi_index(vo.get_tile_id_3d(i, grid, tile), n))
+        assert row0[t] <= perm[i] < row0[t + 1]
 
 
 def test_window_covering_the_grid_is_one_run():
@@ -156,6 +207,13 @@ def test_route_partition_and_select():
     with pytest.raises(vorta.VortaError) as e:
         vorta.vorta_route_partition(plan, np.full(cfg.heads, 3, dtype=np.uint8))
     assert e.value.code == -5
+    for wrong in (routes[:2], np.concatenate([routes, routes])):      # a route vector of the wrong length
+        with pytest.raises(vorta.VortaError) as e:
+            vorta.vorta_route_partition(plan, wrong)
+        assert e.value.code == -1
+        with pytest.raises(vorta.VortaError) as e:
+            vorta.vorta_workspace_bytes(plan, wrong)
+        assert e.value.code == -1
     rng = np.random.default_rng(0)
     alpha = rng.random((64, 3)).astype(np.float32)
     alpha[:8] = [[.4, .4, .2], [.2, .4, .4], [.4, .2, .4], [1 / 3, 1 / 3, 1 / 3], [.5, .3, .2], [.2, .5, .3],
@@ -217,3 +275,44 @@ def test_workspace_layout_is_aligned_and_ordered():
     plan32 = vorta.plan_for(cfg32)
     off32 = vorta.vorta_workspace_layout(plan32, np.array([1, 1], dtype=np.uint8))
     assert off32[1] - off32[0] == 2 * plan32.n_tokens * 64 * 4
+
+
+def test_tensor_arguments_are_checked_before_the_c_call():
+    """The wrappers reject tensors that do not fit the plan -- here with CPU tensors, which fail
+    the first check; the shape, dtype and device checks run on the GPU machine."""
+    import torch
+    cfg = get_config("tiny")
+    plan = vorta.plan_for(cfg)
+    x = torch.zeros(plan.user_shape())
+    for call in (lambda: vorta.vorta_routed_attention_layer(plan, x, x, x, [0, 0]),
+                 lambda: vorta.vorta_soft_mixture_layer(plan, x, x, x, np.full((2, 3), 1 / 3)),
+                 lambda: vorta.vorta_bcs_build_index(plan, x, [2, 2]),
+                 lambda: vorta.vorta_reorder_to_tiles(plan, x, [1, 1])):
+        with pytest.raises(vorta.VortaError) as e:
+            call()
+        assert e.value.code == -1
+    with pytest.raises(vorta.VortaError) as e:
+        vorta.vorta_soft_mixture_layer(plan, x, x, x, np.full((3, 3), 1 / 3))      # gates for 3 heads, plan has 2
+    assert e.value.code == -1 and "alpha" in str(e.value)
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """vorta_host.cpp is plain C++: build it with -fsanitize=address,undefined together with a
+    driver that walks every host entry point over ordinary, clipped, oversized and rejected
+    descriptions, and run it.  Any report makes the driver exit non-zero."""
+    import shutil
+    import subprocess
+    gxx = shutil.which("g++")
+    if gxx is None:
+        pytest.skip("no host compiler")
+    csrc = os.path.join(ROOT, "paper_2505_18809_amd", "csrc")
+    exe = str(tmp_path / "host_sanitized")
+    cmd = [gxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-I", os.path.join(ROOT, "include"), "-I", csrc, os.path.join(csrc, "vorta_host.cpp"),
+           os.path.join(ROOT, "tests", "host_sanitizer_driver.cpp"), "-o", exe]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", LD_PRELOAD="")
+    run = subprocess.run([exe], capture_output=True, text=True, env=env)
+    assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-3000:])
+    assert "host entry points clean" in run.stdout

@@ -111,6 +111,8 @@ def test_constant_values_give_constant_output(route):
     ("sta_mask_1x1x8_tile2_win3.txt", (1, 1, 8), (1, 1, 2), (1, 1, 3)),
     ("sta_mask_2x2x4_tile1x1x2_win1.txt", (2, 2, 4), (1, 1, 2), (1, 1, 1)),
     ("sta_mask_3x1x2_tile1x1x1_win3x1x1.txt", (3, 1, 2), (1, 1, 1), (3, 1, 1)),
+    ("sta_mask_1x1x14_tile2_win3_block.txt", (1, 1, 14), (1, 1, 2), (1, 1, 3)),
+    ("sta_mask_2x1x5_tile1_win2x1x2_block.txt", (2, 1, 5), (1, 1, 1), (2, 1, 2)),
 ])
 def test_mask_hand_worked_fixtures(name, grid, tile, window):
     for mode, want in read_mask_fixture(name).items():
@@ -118,6 +120,43 @@ def test_mask_hand_worked_fixtures(name, grid, tile, window):
         assert (got == want).all(), (name, mode)
         rows = np.stack([vo.sta_mask_row(i, grid, tile, window, mode) for i in range(len(want))])
         assert (rows == want).all()
+        assert all(vo.sta_mask_entry(i, j, grid, tile, window, mode) == want[i, j]
+                   for i in range(len(want)) for j in range(len(want)))
+
+
+def scalar_mask(grid, tile, window, mode):
+    """Algorithm 1 evaluated entry by entry with Python integers, the centre rule written out
+    again here: a check of the oracle's vectorised forms that shares none of their code."""
+    F, H, W = grid
+    L = F * H * W
+    n = [-(-g // t) for g, t in zip(grid, tile)]
+    def tile_of(i):
+        return (i // (H * W) // tile[0], i // W % H // tile[1], i % W // tile[2])
+    def centre(q, a):
+        w = window[a]
+        if mode == "identity":
+            return q
+        if mode == "block":
+            return q - q % w + w // 2
+        return sorted((w // 2, q, max(n[a] - 1 - w // 2, w // 2)))[1]      # the middle one = q clamped
+    M = np.zeros((L, L), dtype=bool)
+    for i in range(L):
+        c = [centre(tile_of(i)[a], a) for a in range(3)]
+        for j in range(L):
+            k = tile_of(j)
+            M[i, j] = all(2 * abs(c[a] - k[a]) <= window[a] for a in range(3))
+    return M
+
+
+@pytest.mark.parametrize("mode", ["clamp", "identity", "block"])
+@pytest.mark.parametrize("grid,tile,window", [((4, 6, 6), (2, 2, 3), (3, 1, 3)), ((3, 5, 7), (1, 2, 3), (2, 3, 5)),
+                                              ((2, 4, 9), (2, 1, 2), (1, 2, 3)), ((5, 7, 6), (2, 3, 4), (3, 3, 3))])
+def test_mask_forms_equal_a_scalar_evaluation(grid, tile, window, mode):
+    want = scalar_mask(grid, tile, window, mode)
+    assert (vo.sta_mask_dense(grid, tile, window, mode) == want).all()
+    for i in range(0, want.shape[0], 5):
+        assert (vo.sta_mask_row(i, grid, tile, window, mode) == want[i]).all()
+        assert all(vo.sta_mask_entry(i, j, grid, tile, window, mode) == want[i, j] for j in range(0, want.shape[1], 3))
 
 
 @pytest.mark.parametrize("window", [(1, 1, 1), (3, 3, 3), (1, 3, 5), (5, 1, 3), (2, 4, 2)])
@@ -181,6 +220,8 @@ def test_mask_covers_everything_when_window_spans_grid():
     for mode in ("clamp", "identity"):
         w = tuple(2 * nd - 1 for nd in n)
         assert vo.sta_mask_dense(grid, tile, w, mode).all()
+    # block reading: one block per axis once w >= n, and its middle tile sees the whole axis
+    assert vo.sta_mask_dense(grid, tile, tuple(nd + (nd + 1) % 2 for nd in n), "block").all()
     # the Tiny benchmark layer: 2x2x2 tiles under a 3x3x3 window is dense
     tiny = get_config("tiny")
     assert vo.tile_grid(tiny.grid, tiny.tile) == (2, 2, 2)
