@@ -7,8 +7,9 @@ path's tests / benchmark may import.
 """
 from .configs import LayerConfig, CONFIGS, get_config, ROUTE_FULL, ROUTE_WINDOW, ROUTE_CORESET
 from .fields import make_qkv, make_routes, blur_matrix
+from .router import make_router_inputs, timestep_embedding
 
 __all__ = [
-    "LayerConfig", "CONFIGS", "get_config", "make_qkv", "make_routes", "blur_matrix",
+    "LayerConfig", "CONFIGS", "get_config", "make_qkv", "make_routes", "blur_matrix", "make_router_inputs", "timestep_embedding",
     "ROUTE_FULL", "ROUTE_WINDOW", "ROUTE_CORESET",
 ]
