@@ -118,8 +118,8 @@ int vorta_plan_destroy(vorta_plan* plan);
 
 /* Set-up step for callers that want no allocation later: uploads the plan's index tables now
  * (blocking hipMalloc + hipMemcpy on the current device, which the plan then belongs to) instead
- * of on the first device call.  Idempotent.  After it, no entry point allocates device memory
- * for this plan. */
+ * of on the first device call, and resolves the address of the library's static scratch on that
+ * device.  Idempotent.  After it, no entry point allocates device memory for this plan. */
 int vorta_plan_upload(vorta_plan* plan);
 
 int vorta_plan_info_get(const vorta_plan* plan, vorta_plan_info* out);
@@ -273,6 +273,22 @@ int vorta_soft_mixture_workspace_bytes(const vorta_plan* plan, size_t* bytes);
 int vorta_soft_mixture_layer(vorta_plan* plan, const void* q, const void* k, const void* v,
                              const float* alpha_host, void* out, void* workspace,
                              size_t workspace_bytes, void* stream);
+
+/* ---- for callers that cannot allocate ------------------------------------------------------- */
+
+/* vorta_routed_attention_layer without a workspace argument and without any allocation, for
+ * callers that must not call hipMalloc: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it.  The internal buffers live in a fixed array of
+ * VORTA_STATIC_SCRATCH_BYTES inside the library's device image (every GPU the library runs on
+ * holds one until the process ends).  Requirements: vorta_plan_upload(plan) has been called (else
+ * VORTA_EINVAL -- this call never uploads), and vorta_workspace_bytes(plan, routes) fits the
+ * array (else VORTA_EWORKSPACE).  All calls on one GPU share the array: two calls whose stream
+ * work overlaps in time race; calls on one stream are ordered.  Nothing in the array needs to
+ * start at zero -- every buffer is fully written before it is read.  Results are those of
+ * vorta_routed_attention_layer, bit for bit. */
+#define VORTA_STATIC_SCRATCH_BYTES (32u << 20)
+int vorta_routed_attention_layer_static(vorta_plan* plan, const void* q, const void* k, const void* v,
+                                        const uint8_t* routes_host, void* out, void* stream);
 
 #ifdef __cplusplus
 }

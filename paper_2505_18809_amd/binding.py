@@ -23,6 +23,7 @@ VORTA_LAYOUT_NHD, VORTA_LAYOUT_HND = 0, 1
 VORTA_CENTER_CLAMP, VORTA_CENTER_IDENTITY, VORTA_CENTER_BLOCK = 0, 1, 2
 VORTA_MAX_HEADS = 128
 VORTA_FEAT_USER_LAYOUT = -1
+VORTA_STATIC_SCRATCH_BYTES = 32 << 20
 
 SYMBOLS = [
     "vorta_strerror", "vorta_last_error", "vorta_plan_create", "vorta_plan_destroy", "vorta_plan_info_get",
@@ -31,7 +32,7 @@ SYMBOLS = [
     "vorta_reorder_to_tiles", "vorta_reorder_from_tiles",
     "vorta_bcs_build_index", "vorta_bcs_pool", "vorta_attention_routed", "vorta_scatter_back",
     "vorta_workspace_bytes", "vorta_workspace_layout", "vorta_routed_attention_layer",
-    "vorta_soft_mixture_workspace_bytes", "vorta_soft_mixture_layer",
+    "vorta_soft_mixture_workspace_bytes", "vorta_soft_mixture_layer", "vorta_routed_attention_layer_static",
 ]
 
 
@@ -439,6 +440,16 @@ def vorta_routed_attention_layer(plan: Plan, q, k, v, routes, out=None, workspac
     _check(load_library().vorta_routed_attention_layer(
         plan.handle, _ptr(q), _ptr(k), _ptr(v), _u8p(r), _ptr(out), _ptr(workspace),
         ctypes.c_size_t(workspace.numel()), _stream(stream)))
+    return out
+
+
+def vorta_routed_attention_layer_static(plan: Plan, q, k, v, routes, out, stream=None):
+    """The layer call for callers that cannot allocate: no workspace argument (the library's
+    static scratch is used), `out` must be given, vorta_plan_upload(plan) must have been called."""
+    r = _routes(routes, plan)
+    _check_tensors(plan, q=plan._user(q), k=plan._user(k), v=plan._user(v), out=plan._user(out))
+    _check(load_library().vorta_routed_attention_layer_static(
+        plan.handle, _ptr(q), _ptr(k), _ptr(v), _u8p(r), _ptr(out), _stream(stream)))
     return out
 
 

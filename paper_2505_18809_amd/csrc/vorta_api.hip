@@ -19,6 +19,31 @@ static int check_ptr(const void* p, const char* name) {
     if (int rc_ = (expr)) return rc_; \
   } while (0)
 
+// Scratch of the entry point that allocates nothing: a fixed array in the library's own device
+// image, one copy per GPU at an address of its own.  In host code the array's name is only a
+// stand-in for the symbol; the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[VORTA_STATIC_SCRATCH_BYTES];
+
+static int static_scratch(void** out) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static void* ptr[MAX_DEVICES] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(VORTA_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(VORTA_EINVAL, "device %d: at most %d devices", dev, MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* found = nullptr;
+    e = hipGetSymbolAddress(&found, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !found)
+      return fail(VORTA_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    ptr[dev] = found;
+  }
+  *out = ptr[dev];
+  return VORTA_OK;
+}
+
 static int begin(vorta_plan* p, const uint8_t* routes, RouteLists* rl) {
   clear_error();
   VORTA_TRY(split_routes(p, routes, rl));
@@ -293,7 +318,9 @@ int vorta_soft_mixture_layer(vorta_plan* p, const void* q, const void* k, const 
 int vorta_plan_upload(vorta_plan* p) {
   clear_error();
   if (!p) return fail(VORTA_EINVAL, "null plan");
-  return ensure_device_tables(p);
+  VORTA_TRY(ensure_device_tables(p));
+  void* scratch_ptr = nullptr;
+  return static_scratch(&scratch_ptr);     // also resolves the static scratch of this device
 }
 
 int vorta_router_device(const float* t_emb, const float* w_r, int32_t n_steps, int32_t d_t, int32_t heads,
@@ -309,6 +336,34 @@ int vorta_router_device(const float* t_emb, const float* w_r, int32_t n_steps, i
     if (e != hipSuccess) return fail(VORTA_EHIP, "copy of the routes to the host: %s", hipGetErrorString(e));
   }
   return VORTA_OK;
+}
+
+int vorta_routed_attention_layer_static(vorta_plan* p, const void* q, const void* k, const void* v,
+                                        const uint8_t* routes, void* out, void* stream) {
+  clear_error();
+  RouteLists rl;
+  VORTA_TRY(split_routes(p, routes, &rl));
+  {
+    std::lock_guard<std::mutex> lock(p->mu);
+    if (!p->on_device)
+      return fail(VORTA_EINVAL, "the plan's tables are not on the device: call vorta_plan_upload once first (this call allocates nothing)");
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(VORTA_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev != p->device) return fail(VORTA_EINVAL, "plan belongs to device %d, current device is %d", p->device, dev);
+  }
+  VORTA_TRY(check_ptr(q, "q")); VORTA_TRY(check_ptr(k, "k"));
+  VORTA_TRY(check_ptr(v, "v")); VORTA_TRY(check_ptr(out, "out"));
+  size_t need = 0;
+  VORTA_TRY(vorta_workspace_bytes(p, routes, &need));
+  if (need > VORTA_STATIC_SCRATCH_BYTES)
+    return fail(VORTA_EWORKSPACE, "this layer needs %zu bytes of scratch, the static buffer holds %zu: use vorta_routed_attention_layer with a workspace",
+                need, (size_t)VORTA_STATIC_SCRATCH_BYTES);
+  void* scratch_ptr = nullptr;
+  VORTA_TRY(static_scratch(&scratch_ptr));
+  Carved c;
+  VORTA_TRY(carve(p, routes, scratch_ptr, VORTA_STATIC_SCRATCH_BYTES, &c));
+  return layer(p, rl, q, k, v, routes, out, c, stream);
 }
 
 }  // extern "C"
