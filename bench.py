@@ -25,10 +25,25 @@ if ROOT not in sys.path:
 
 METRIC = "ms per routed attention layer + effective TFLOP/s (% MFMA peak) at 75.6k tokens"
 MFMA_PEAK_TFLOPS = {"bf16": 2516.6, "fp32": 157.3}      # MI355X dense peaks
-# HBM bytes per launch of the dominant kernel on the wan720p workload, from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs of this command, each scaled by what the counter reads for a
-# plain 1 GiB copy (profiles/layer_wan720p_hbm_traffic.txt): (8,589,710 + 264,600) KiB.
-ATTN_TRAFFIC_BYTES = (8589710 + 264600) * 1024
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "layer_wan720p_hbm_traffic.txt")
+
+
+def profiled_traffic(kernel, workload, layout):
+    """HBM-side bytes per launch of `kernel`, read from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by what the counters read for a
+    plain 1 GiB copy).  It is a recorded figure, not a live one: it is reported only for the
+    command the profile was taken with (wan720p, HND layout) and names its source; None if the
+    summary is missing or has no row for the kernel."""
+    if workload != "wan720p" or layout != 1 or not os.path.exists(TRAFFIC_PROFILE):
+        return None
+    for line in open(TRAFFIC_PROFILE):
+        if line.startswith(kernel):
+            nums = [int(tok.replace(",", "")) for tok in line[len(kernel):].replace("/", " ").split()
+                    if tok.replace(",", "").isdigit()]
+            if len(nums) >= 5:            # FETCH raw, FETCH KiB, WRITE KiB, algorithmic read KiB, algorithmic write KiB
+                return {"bytes": (nums[1] + nums[2]) * 1024, "algorithmic_bytes": (nums[3] + nums[4]) * 1024,
+                        "source": os.path.relpath(TRAFFIC_PROFILE, ROOT)}
+    return None
 
 
 def layer_flops(cfg, plan, routes):
@@ -281,6 +296,7 @@ def main():
         win_ms = e0.elapsed_time(e1) / args.steps
         del sq, sk, sv, so
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+    traffic = profiled_traffic(dom["kernel"], args.workload, args.layout)
     result = {
         "metric": METRIC,
         "value": flops / (ms * 1e-3) / 1e12,
@@ -300,7 +316,9 @@ def main():
                      "launch": f"{counts[0]} dense + {counts[2]} core-set heads of the layer (the window heads are a separate launch)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "flops_per_launch": dom["flops"], "ms_per_launch": dom["ms"],
-                     "traffic": ATTN_TRAFFIC_BYTES if args.workload == "wan720p" else None},
+                     "traffic": traffic["bytes"] if traffic else None,
+                     "traffic_algorithmic": traffic["algorithmic_bytes"] if traffic else None,
+                     "traffic_source": traffic["source"] if traffic else None},
         "dominant_kernel_on_zero_operands": ({"ms_per_launch": dom["zero_ms"],
                                               "TFLOP/s": dom["flops"] / (dom["zero_ms"] * 1e-3) / 1e12,
                                               "frac": dom["flops"] / (dom["zero_ms"] * 1e-3) / 1e12 / peak,
