@@ -13,6 +13,8 @@ What each function follows:
                               complexity paragraph)
   routing ................... Eq. 3 (gates) and Eq. 4 (hard selection)
   soft mixture .............. Eq. 5
+  rotary embedding .......... named in section 3.3 as part of the block, not defined there: the
+                              axial 3-D form is a reading (see the section on it below)
 
 Readings taken where the paper is silent (kept in one place so a reader can
 check them):
@@ -41,7 +43,11 @@ against brute force, closed forms or special cases that reduce to textbook
 softmax attention / average pooling.  The whole core-set route has no
 published numeric example: it is pinned to those special cases and to a
 scalar re-derivation on tiny grids, and beyond that is "parity unpinned"
-against the authors' own code.
+against the authors' own code.  The rotary embedding is pinned by what the
+mathematics fixes (norms, dependence on relative position only, composition,
+the identity at the origin, a hand-computed 2-D turn); which channels belong to
+which axis and how channels pair up is a reading: "parity unpinned" against the
+authors' models.
 """
 from dataclasses import dataclass
 from typing import Dict, Optional, Sequence, Tuple
@@ -62,6 +68,8 @@ class LayerSpec:
     n_text: int = 0
     scale: Optional[float] = None                # None -> 1/sqrt(head_dim)
     center_mode: str = "clamp"
+    rope_dims: Optional[Tuple[int, int, int]] = None   # channels rotated by the F, H, W position; None = no RoPE
+    rope_theta: float = 10000.0
 
     @property
     def n_video(self) -> int:
@@ -168,6 +176,57 @@ def sta_mask_dense(grid, tile, window, mode: str = "clamp") -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# rotary position embedding on the 3-D grid
+#
+# The paper's block applies RoPE to Q and K and leaves it out of its equations "for clarity"
+# (section 3.3, "Inference-time routing strategy"), so the rotation itself is a reading: the
+# axial 3-D form video DiTs use.  The first rope_dims[0] channels of a head are rotated by the
+# token's frame index, the next rope_dims[1] by its row, the next rope_dims[2] by its column;
+# channels beyond their sum and text tokens are left alone.  Inside an axis' span, channels
+# (2i, 2i+1) form a pair that is turned by the angle  pos * theta^(-2i / span).
+# Core-set branch: pool() acts on the block's input, i.e. before the rotation (pooling commutes
+# with the linear projections, not with RoPE); a core-set row is then rotated with the position
+# of the token that owns its slot (a merged centre keeps the centre's position).
+# --------------------------------------------------------------------------
+
+def rope_angles(positions, span: int, theta: float) -> np.ndarray:
+    """[n] integer positions -> [n, span / 2] angles pos * theta^(-2 i / span)."""
+    i = np.arange(span // 2, dtype=np.float64)
+    return np.asarray(positions, dtype=np.float64)[:, None] * theta ** (-2.0 * i / span)[None, :]
+
+
+def rope_rotate(X, coords, rope_dims, theta: float = 10000.0) -> np.ndarray:
+    """X: [n, d]; coords: [n, 3] integer (f, h, w) of every row.  Returns the rotated copy."""
+    X = np.asarray(X, dtype=np.float64)
+    coords = np.asarray(coords)
+    assert all(s % 2 == 0 and s >= 0 for s in rope_dims) and sum(rope_dims) <= X.shape[1]
+    out = X.copy()
+    start = 0
+    for axis, span in enumerate(rope_dims):
+        if span:
+            ang = rope_angles(coords[:, axis], span, theta)
+            a, b = X[:, start:start + span:2], X[:, start + 1:start + span:2]
+            out[:, start:start + span:2] = a * np.cos(ang) - b * np.sin(ang)
+            out[:, start + 1:start + span:2] = a * np.sin(ang) + b * np.cos(ang)
+        start += span
+    return out
+
+
+def rope_video_rows(X, spec: "LayerSpec", token_ids=None) -> np.ndarray:
+    """Rotate the rows of X that belong to video tokens: row r holds token token_ids[r]
+    (default r itself); rows past the video tokens (text) are returned unchanged."""
+    X = np.asarray(X, dtype=np.float64)
+    if spec.rope_dims is None:
+        return X
+    n = X.shape[0] if token_ids is None else len(token_ids)
+    ids = np.arange(min(n, spec.n_video)) if token_ids is None else np.asarray(token_ids, dtype=np.int64)
+    coords = np.array([token_coord(int(i), spec.grid) for i in ids]).reshape(-1, 3)
+    out = X.copy()
+    out[:len(ids)] = rope_rotate(X[:len(ids)], coords, spec.rope_dims, spec.rope_theta)
+    return out
+
+
+# --------------------------------------------------------------------------
 # softmax attention (Eq. 2)
 # --------------------------------------------------------------------------
 
@@ -199,8 +258,9 @@ def _all_rows(n: int, rows) -> np.ndarray:
 
 
 def full_attention(Q, K, V, spec: LayerSpec, rows=None) -> np.ndarray:
-    """Route 0.  Q, K, V: [N, d] of one head.  Returns O[rows]."""
-    Q = np.asarray(Q, dtype=np.float64)
+    """Route 0.  Q, K, V: [N, d] of one head (before RoPE, if the spec has one).  Returns O[rows]."""
+    Q = rope_video_rows(Q, spec)
+    K = rope_video_rows(K, spec)
     rows = _all_rows(Q.shape[0], rows)
     return attention_rows(Q[rows], K, V, _scale(spec, Q.shape[1]))
 
@@ -208,8 +268,8 @@ def full_attention(Q, K, V, spec: LayerSpec, rows=None) -> np.ndarray:
 def window_attention(Q, K, V, spec: LayerSpec, rows=None) -> np.ndarray:
     """Route 1: softmax attention restricted to Algorithm 1's mask; text
     tokens (if any) are unmasked in both directions."""
-    Q = np.asarray(Q, dtype=np.float64)
-    K = np.asarray(K, dtype=np.float64)
+    Q = rope_video_rows(Q, spec)
+    K = rope_video_rows(K, spec)
     V = np.asarray(V, dtype=np.float64)
     L, N = spec.n_video, Q.shape[0]
     assert N == L + spec.n_text
@@ -330,8 +390,9 @@ def coreset_attention(Q, K, V, spec: LayerSpec, rows=None, feat=None, index=None
         index = bcs_select(f, spec.grid, spec.bucket, spec.keep_num, spec.keep_den)
     keep_idx, assign = index[0], index[1]
     Lc = len(keep_idx)
-    Qc = np.concatenate([bcs_pool(Q[:L], keep_idx, assign), Q[L:]])
-    Kc = np.concatenate([bcs_pool(K[:L], keep_idx, assign), K[L:]])
+    # pool first (on the un-rotated rows), then rotate each core-set row with its slot owner's position
+    Qc = np.concatenate([rope_video_rows(bcs_pool(Q[:L], keep_idx, assign), spec, keep_idx), Q[L:]])
+    Kc = np.concatenate([rope_video_rows(bcs_pool(K[:L], keep_idx, assign), spec, keep_idx), K[L:]])
     Vc = np.concatenate([bcs_pool(V[:L], keep_idx, assign), V[L:]])
     # slot every output row reads from: video tokens via assign, text tokens their own
     src = np.concatenate([assign.astype(np.int64), Lc + np.arange(spec.n_text)])

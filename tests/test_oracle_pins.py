@@ -468,6 +468,102 @@ def test_coreset_route_matches_scalar_rederivation(grid, n_text, keep):
     assert np.abs(got - vo.full_attention(Q, K, V, spec)).max() > 1e-3
 
 
+# ------------------------------------------------------------------- RoPE ---
+
+def complex_rope(X, coords, rope_dims, theta):
+    """The same rotation written with complex numbers: channel pairs are complex values that are
+    multiplied by exp(i * position * rate).  Python scalars only."""
+    out = [list(map(float, row)) for row in X]
+    for r, (row, pos) in enumerate(zip(X, coords)):
+        start = 0
+        for axis, span in enumerate(rope_dims):
+            for i in range(span // 2):
+                z = complex(row[start + 2 * i], row[start + 2 * i + 1])
+                z *= complex(math.cos(pos[axis] * theta ** (-2 * i / span)), math.sin(pos[axis] * theta ** (-2 * i / span)))
+                out[r][start + 2 * i], out[r][start + 2 * i + 1] = z.real, z.imag
+            start += span
+    return np.array(out)
+
+
+def test_rope_hand_computed_turns_and_what_it_leaves_alone():
+    # one pair, span 2: the rate is theta^0 = 1, so position p turns (1, 0) by p radians
+    X = np.array([[1.0, 0.0, 7.0], [0.0, 2.0, 7.0]])
+    Y = vo.rope_rotate(X, [[3, 0, 0], [3, 0, 0]], (2, 0, 0), 10000.0)
+    np.testing.assert_allclose(Y, [[math.cos(3), math.sin(3), 7.0], [-2 * math.sin(3), 2 * math.cos(3), 7.0]], atol=1e-15)
+    # span 4 at theta = 10000: pair 0 turns by p, pair 1 by p / 100; the H axis uses the row index
+    X = np.array([[1.0, 0.0, 1.0, 0.0, 5.0, 6.0]])
+    Y = vo.rope_rotate(X, [[9, 50, 2]], (0, 4, 0), 10000.0)
+    np.testing.assert_allclose(Y, [[math.cos(50), math.sin(50), math.cos(0.5), math.sin(0.5), 5.0, 6.0]], atol=1e-14)
+    # the origin is the identity; channels past the three spans never move
+    X = np.random.default_rng(30).standard_normal((4, 12))
+    np.testing.assert_array_equal(vo.rope_rotate(X, np.zeros((4, 3), int), (4, 2, 4)), X)
+    Y = vo.rope_rotate(X, [[1, 2, 3]] * 4, (4, 2, 4))
+    np.testing.assert_array_equal(Y[:, 10:], X[:, 10:])
+    assert np.abs(Y[:, :10] - X[:, :10]).min() > 0
+    # moving along one axis only changes that axis' channels
+    Z = vo.rope_rotate(X, [[1, 2, 8]] * 4, (4, 2, 4))
+    np.testing.assert_array_equal(Z[:, :6], Y[:, :6])
+    assert np.abs(Z[:, 6:10] - Y[:, 6:10]).min() > 0
+
+
+def test_rope_is_a_rotation_that_depends_on_relative_position_only():
+    rng = np.random.default_rng(31)
+    dims, theta = (4, 6, 6), 100.0
+    q, k = rng.standard_normal((2, 1, 20))
+    pi, pj, shift = np.array([[3, 7, 2]]), np.array([[1, 4, 9]]), np.array([[5, 11, 6]])
+    Rq, Rk = vo.rope_rotate(q, pi, dims, theta), vo.rope_rotate(k, pj, dims, theta)
+    # norms of every pair survive
+    np.testing.assert_allclose(Rq[0, 0:16:2] ** 2 + Rq[0, 1:16:2] ** 2, q[0, 0:16:2] ** 2 + q[0, 1:16:2] ** 2, atol=1e-13)
+    # <R_i q, R_j k> is unchanged when both positions move together, and equals <q, R_(j-i) k>
+    moved = vo.rope_rotate(q, pi + shift, dims, theta) @ vo.rope_rotate(k, pj + shift, dims, theta).T
+    np.testing.assert_allclose(moved, Rq @ Rk.T, atol=1e-12)
+    np.testing.assert_allclose(q @ vo.rope_rotate(k, pj - pi, dims, theta).T, Rq @ Rk.T, atol=1e-12)
+    assert abs((vo.rope_rotate(q, pi + shift, dims, theta) @ Rk.T - Rq @ Rk.T).item()) > 1e-3
+    # turning by a then by b is turning by a + b
+    twice = vo.rope_rotate(vo.rope_rotate(q, pi, dims, theta), shift, dims, theta)
+    np.testing.assert_allclose(twice, vo.rope_rotate(q, pi + shift, dims, theta), atol=1e-13)
+    # against the complex-number form, scalar Python
+    X = rng.standard_normal((6, 20))
+    coords = rng.integers(0, 30, (6, 3))
+    np.testing.assert_allclose(vo.rope_rotate(X, coords, dims, theta), complex_rope(X.tolist(), coords.tolist(), dims, theta),
+                               atol=1e-13)
+
+
+@pytest.mark.parametrize("n_text", [0, 3])
+def test_routes_with_rope_rotate_queries_and_keys_at_the_right_point(n_text):
+    """Routes 0 and 1: plain attention on Q and K rotated by their own grid position (text rows
+    unrotated).  Route 2: pooling acts before the rotation and a core-set row turns with the
+    position of the token that owns its slot -- rebuilt here from pool(), the complex form and
+    plain attention."""
+    rng = np.random.default_rng(32)
+    grid, d = (2, 3, 4), 8
+    L = 24
+    dims, theta = (2, 2, 4), 50.0
+    Q, K, V = (np.concatenate([smooth_field(rng, grid, d), rng.standard_normal((n_text, d))]) for _ in range(3))
+    spec = vo.LayerSpec(grid=grid, tile=(1, 3, 2), window=(1, 1, 1), n_text=n_text, scale=0.3, rope_dims=dims, rope_theta=theta)
+    plain = vo.LayerSpec(grid=grid, tile=(1, 3, 2), window=(1, 1, 1), n_text=n_text, scale=0.3)
+    coords = [list(vo.token_coord(i, grid)) for i in range(L)]
+    turn = lambda X, c: np.concatenate([complex_rope(X[:len(c)].tolist(), c, dims, theta), X[len(c):]])
+    Qr, Kr = turn(Q, coords), turn(K, coords)
+    np.testing.assert_allclose(vo.full_attention(Q, K, V, spec), vo.full_attention(Qr, Kr, V, plain), atol=1e-12)
+    np.testing.assert_allclose(vo.window_attention(Q, K, V, spec), vo.window_attention(Qr, Kr, V, plain), atol=1e-12)
+    assert np.abs(vo.full_attention(Q, K, V, spec) - vo.full_attention(Q, K, V, plain)).max() > 1e-3
+    keep_idx, assign, _ = vo.bcs_select(K[:L], grid, spec.bucket)           # selection sees the un-rotated keys
+    slot_coords = [coords[i] for i in keep_idx]
+    Qc = np.concatenate([turn(vo.bcs_pool(Q[:L], keep_idx, assign), slot_coords), Q[L:]])
+    Kc = np.concatenate([turn(vo.bcs_pool(K[:L], keep_idx, assign), slot_coords), K[L:]])
+    Vc = np.concatenate([vo.bcs_pool(V[:L], keep_idx, assign), V[L:]])
+    Oc = vo.attention_rows(Qc, Kc, Vc, 0.3)
+    want = np.concatenate([Oc[assign], Oc[len(keep_idx):]])
+    np.testing.assert_allclose(vo.coreset_attention(Q, K, V, spec), want, atol=1e-12)
+    # rotate-then-pool would be something else
+    other = vo.coreset_attention(Qr, Kr, V, plain, feat=K)
+    assert np.abs(other - want).max() > 1e-3
+    # rows= picks rows of the same result
+    np.testing.assert_allclose(vo.coreset_attention(Q, K, V, spec, rows=[L + n_text - 1, 0, 5]), want[[L + n_text - 1, 0, 5]],
+                               atol=1e-13)
+
+
 # ---------------------------------------------------------------- routing ---
 
 def test_hard_route_follows_eq4_and_sends_ties_to_full():
