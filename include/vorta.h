@@ -85,6 +85,16 @@ typedef struct vorta_layer_desc {
                                at most 64 tokens after clipping to the grid                    */
   int32_t keep_num, keep_den; /* core-set ratio r = keep_num/keep_den, 0 < r <= 1 (paper: 1/2) */
   float softmax_scale;      /* <= 0 selects 1/sqrt(head_dim)                                 */
+  int32_t rope_dims[3];     /* rotary position embedding of Q and K (section 3.3 names it as part of
+                               the block and omits it from the equations; the axial 3-D form is this
+                               library's reading): the first rope_dims[0] channels of a head turn with
+                               the token's frame index, the next rope_dims[1] with its row, the next
+                               rope_dims[2] with its column; channels (2i, 2i+1) of an axis' span s
+                               turn by position * rope_theta^(-2i / s).  Even, >= 0, sum <= head_dim;
+                               channels beyond the sum and text tokens do not turn.  All zero: the
+                               caller's q and k are used as they are (no RoPE, or already applied --
+                               which is only right if no head takes route 2, see below).           */
+  float rope_theta;         /* <= 0 selects 10000                                             */
 } vorta_layer_desc;
 
 typedef struct vorta_plan vorta_plan;   /* opaque */
@@ -209,9 +219,19 @@ int vorta_bcs_build_index(vorta_plan* plan, const void* feat, int64_t feat_head_
 
 /* pool(): dst[slot][s] = mean of src rows assigned to core-set slot s (a kept token alone,
  * or a centre with the tokens pruned into it), then the text rows unchanged.  src: user
- * layout; dst: [n_lr][L_c + n_text][d].  Call once per tensor (Q, K, V). */
+ * layout; dst: [n_lr][L_c + n_text][d].  Call once per tensor (Q, K, V).
+ * rotate != 0 (for Q and K of a plan with rope_dims): the pooled row is then turned by the
+ * rotary embedding at the position of the token that owns the slot, keep_idx[s] -- pooling
+ * acts on the block's input and commutes with the projections but not with RoPE, so on route 2
+ * the rotation comes after pool(); mean and rotation are computed in fp64 and rounded once. */
 int vorta_bcs_pool(vorta_plan* plan, const void* src, const uint8_t* routes_host,
-                   const int32_t* keep_idx, const int32_t* assign, void* dst, void* stream);
+                   const int32_t* keep_idx, const int32_t* assign, int32_t rotate, void* dst, void* stream);
+
+/* Rotary embedding for the heads on routes 0 and 1: dst rows of those heads = src rows turned
+ * at their token's grid position (text rows copied).  src, dst: user layout (dst rows of other
+ * heads are not touched); a no-op returning VORTA_OK when the plan has no rope_dims.  The layer
+ * call runs it on Q and K; route 2 rotates inside vorta_bcs_pool instead. */
+int vorta_rope_apply(vorta_plan* plan, const void* src, const uint8_t* routes_host, void* dst, void* stream);
 
 /* Buffers of the fused attention launch.  Unused groups may be NULL when no head takes
  * that route.  bf16 only: q_t, k_t, v_t and o_t may ALL be NULL although heads take route 1 --
@@ -219,7 +239,8 @@ int vorta_bcs_pool(vorta_plan* plan, const void* src, const uint8_t* routes_host
  * its output rows straight to their places in `out` (no tile-ordered copies, no reorder
  * passes); vorta_scatter_back is then called with o_t = NULL.  This is what the layer call does. */
 typedef struct vorta_attn_io {
-  const void *q, *k, *v;        /* user layout; read by route-0 heads                          */
+  const void *q, *k, *v;        /* user layout; read by route-0 heads (q, k as attention is to see
+                                   them: after vorta_rope_apply if the plan has rope_dims)      */
   void* out;                    /* user layout; route-0 heads write their rows here            */
   const void *q_t, *k_t, *v_t;  /* [n_win][N][d] tile order (vorta_reorder_to_tiles)           */
   void* o_t;                    /* [n_win][N][d] tile order                                    */
@@ -249,13 +270,16 @@ int vorta_scatter_back(vorta_plan* plan, const uint8_t* routes_host, const void*
 int vorta_workspace_bytes(const vorta_plan* plan, const uint8_t* routes_host, size_t* bytes);
 
 /* Byte offsets of the internal buffers inside the workspace, in the order
- * q_t,k_t,v_t,o_t,q_c,k_c,v_c,o_c,keep_idx,assign (for inspection by tests). */
-int vorta_workspace_layout(const vorta_plan* plan, const uint8_t* routes_host, size_t offsets[10]);
+ * q_t,k_t,v_t,o_t,q_c,k_c,v_c,o_c,keep_idx,assign,q_r,k_r (for inspection by tests); q_r and
+ * k_r are the rotated copies of Q and K (user layout, empty without rope_dims). */
+int vorta_workspace_layout(const vorta_plan* plan, const uint8_t* routes_host, size_t offsets[12]);
 
 /* One attention layer under hard routing (Eq. 4; section 3.3 "Inference-time routing
  * strategy"): every head runs the branch its route names -- Eq. 2, Algorithm 1 or the core-set
  * branch of section 3.2.  reorder + index build + pool + fused attention + scatter back, all on
- * `stream`: q, k, v (user layout) -> out (user layout).  The BCS feature is K. */
+ * `stream`: q, k, v (user layout) -> out (user layout).  The BCS feature is K.  With rope_dims,
+ * q and k are the projections BEFORE the rotary embedding: routes 0 and 1 attend on rotated
+ * copies, route 2 selects and pools on the rows as given and rotates the pooled rows. */
 int vorta_routed_attention_layer(vorta_plan* plan, const void* q, const void* k, const void* v,
                                  const uint8_t* routes_host, void* out, void* workspace,
                                  size_t workspace_bytes, void* stream);

@@ -30,7 +30,7 @@ SYMBOLS = [
     "vorta_tile_permutation", "vorta_tile_row0", "vorta_window_boxes", "vorta_window_runs", "vorta_bcs_slot_bases",
     "vorta_plan_upload", "vorta_route_partition", "vorta_router_gates", "vorta_route_select", "vorta_router_device",
     "vorta_reorder_to_tiles", "vorta_reorder_from_tiles",
-    "vorta_bcs_build_index", "vorta_bcs_pool", "vorta_attention_routed", "vorta_scatter_back",
+    "vorta_bcs_build_index", "vorta_bcs_pool", "vorta_rope_apply", "vorta_attention_routed", "vorta_scatter_back",
     "vorta_workspace_bytes", "vorta_workspace_layout", "vorta_routed_attention_layer",
     "vorta_soft_mixture_workspace_bytes", "vorta_soft_mixture_layer", "vorta_routed_attention_layer_static",
 ]
@@ -50,6 +50,7 @@ class vorta_layer_desc(ctypes.Structure):
         ("tile", ctypes.c_int32 * 3), ("window", ctypes.c_int32 * 3), ("center_mode", ctypes.c_int32),
         ("bucket", ctypes.c_int32 * 3), ("keep_num", ctypes.c_int32), ("keep_den", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float),
+        ("rope_dims", ctypes.c_int32 * 3), ("rope_theta", ctypes.c_float),
     ]
 
 
@@ -199,13 +200,14 @@ class Plan:
 
 def vorta_plan_create(grid, heads, head_dim, dtype, tile, window, *, n_text=0, layout=VORTA_LAYOUT_HND,
                       center_mode=VORTA_CENTER_CLAMP, bucket=(2, 3, 2), keep_num=1, keep_den=2,
-                      softmax_scale=0.0) -> Plan:
+                      softmax_scale=0.0, rope_dims=(0, 0, 0), rope_theta=0.0) -> Plan:
     lib = load_library()
     if isinstance(dtype, str):
         dtype = {"fp32": VORTA_F32, "bf16": VORTA_BF16}[dtype]
     d = vorta_layer_desc(grid[0], grid[1], grid[2], n_text, heads, head_dim, dtype, layout,
                          (ctypes.c_int32 * 3)(*tile), (ctypes.c_int32 * 3)(*window), center_mode,
-                         (ctypes.c_int32 * 3)(*bucket), keep_num, keep_den, softmax_scale)
+                         (ctypes.c_int32 * 3)(*bucket), keep_num, keep_den, softmax_scale,
+                         (ctypes.c_int32 * 3)(*(rope_dims or (0, 0, 0))), rope_theta)
     handle = ctypes.c_void_p()
     _check(lib.vorta_plan_create(ctypes.byref(d), ctypes.byref(handle)))
     return Plan(handle, d)
@@ -215,7 +217,8 @@ def plan_for(cfg, layout=VORTA_LAYOUT_HND, **over) -> Plan:
     """Plan for a synth_inputs.LayerConfig-like object (attribute access only)."""
     kw = dict(grid=cfg.grid, heads=cfg.heads, head_dim=cfg.head_dim, dtype=cfg.dtype, tile=cfg.tile,
               window=cfg.window, n_text=cfg.n_text, layout=layout, bucket=cfg.bucket,
-              keep_num=cfg.keep_num, keep_den=cfg.keep_den)
+              keep_num=cfg.keep_num, keep_den=cfg.keep_den,
+              rope_dims=getattr(cfg, "rope_dims", None) or (0, 0, 0), rope_theta=getattr(cfg, "rope_theta", 0.0))
     kw.update(over)
     return vorta_plan_create(**kw)
 
@@ -378,7 +381,18 @@ def vorta_bcs_build_index(plan: Plan, feat: torch.Tensor, routes, keep_idx=None,
     return keep_idx, assign
 
 
-def vorta_bcs_pool(plan: Plan, src: torch.Tensor, routes, keep_idx, assign, dst=None, stream=None):
+def vorta_rope_apply(plan: Plan, src: torch.Tensor, routes, dst: torch.Tensor = None, stream=None):
+    """Rows of the heads on routes 0 and 1, turned by the plan's rotary embedding (other heads'
+    rows of dst are left as they are: a fresh dst holds whatever torch.empty_like gives)."""
+    r = _routes(routes, plan)
+    if dst is None:
+        dst = torch.empty_like(src)
+    _check_tensors(plan, src=plan._user(src), dst=plan._user(dst))
+    _check(load_library().vorta_rope_apply(plan.handle, _ptr(src), _u8p(r), _ptr(dst), _stream(stream)))
+    return dst
+
+
+def vorta_bcs_pool(plan: Plan, src: torch.Tensor, routes, keep_idx, assign, dst=None, stream=None, rotate=False):
     r = _routes(routes, plan)
     n = _count(r, 2)
     if dst is None:
@@ -386,7 +400,7 @@ def vorta_bcs_pool(plan: Plan, src: torch.Tensor, routes, keep_idx, assign, dst=
     _check_tensors(plan, src=plan._user(src), keep_idx=(keep_idx, (n, plan.n_core), torch.int32),
                    assign=(assign, (n, plan.n_video), torch.int32), dst=plan._core(dst, n))
     _check(load_library().vorta_bcs_pool(plan.handle, _ptr(src), _u8p(r), _ptr(keep_idx), _ptr(assign),
-                                         _ptr(dst), _stream(stream)))
+                                         ctypes.c_int32(1 if rotate else 0), _ptr(dst), _stream(stream)))
     return dst
 
 
@@ -421,7 +435,7 @@ def vorta_workspace_bytes(plan: Plan, routes) -> int:
 
 def vorta_workspace_layout(plan: Plan, routes) -> Sequence[int]:
     r = _routes(routes, plan)
-    off = (ctypes.c_size_t * 10)()
+    off = (ctypes.c_size_t * 12)()
     _check(load_library().vorta_workspace_layout(plan.handle, _u8p(r), off))
     return list(off)
 

@@ -112,16 +112,16 @@ static int attention(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* i
 }
 
 struct Carved {
-  char* buf[10];
+  char* buf[12];
 };
 
 static int carve(const vorta_plan* p, const uint8_t* routes, void* workspace, size_t bytes, Carved* c) {
-  size_t need = 0, off[10];
+  size_t need = 0, off[12];
   VORTA_TRY(vorta_workspace_bytes(p, routes, &need));
   if (bytes < need) return fail(VORTA_EWORKSPACE, "workspace has %zu bytes, need %zu", bytes, need);
   VORTA_TRY(check_ptr(workspace, "workspace"));
   VORTA_TRY(vorta_workspace_layout(p, routes, off));
-  for (int i = 0; i < 10; ++i) c->buf[i] = (char*)workspace + off[i];
+  for (int i = 0; i < 12; ++i) c->buf[i] = (char*)workspace + off[i];
   return VORTA_OK;
 }
 
@@ -133,18 +133,27 @@ static int layer(vorta_plan* p, const RouteLists& rl, const void* q, const void*
   // scatters its output rows the same way, so the reorder passes and the tile-ordered copies
   // are only used by the fp32 path
   const bool gather = p->d.dtype == VORTA_BF16;
+  // routes 0 and 1 with a rotary embedding: attention reads rotated copies of Q and K
+  const void *q_att = q, *k_att = k;
+  if (p->rope && rl.count[0] + rl.count[1] > 0) {
+    VORTA_TRY(launch_rope_rows(p, rl, q, c.buf[10], stream));
+    VORTA_TRY(launch_rope_rows(p, rl, k, c.buf[11], stream));
+    q_att = c.buf[10];
+    k_att = c.buf[11];
+  }
   if (!gather) {
-    VORTA_TRY(launch_reorder(p, rl, q, c.buf[0], true, stream));
-    VORTA_TRY(launch_reorder(p, rl, k, c.buf[1], true, stream));
+    VORTA_TRY(launch_reorder(p, rl, q_att, c.buf[0], true, stream));
+    VORTA_TRY(launch_reorder(p, rl, k_att, c.buf[1], true, stream));
     VORTA_TRY(launch_reorder(p, rl, v, c.buf[2], true, stream));
   }
-  // route 2: core-set index on K, then pool Q, K, V
+  // route 2: core-set index on K as given (before the rotation), then pool Q, K, V; the
+  // pooled rows of Q and K are rotated at their slot owner's position
   VORTA_TRY(launch_bcs_index(p, rl, user_tensor(p, k), keep_idx, assign, stream));
-  VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, c.buf[4], stream));
-  VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, c.buf[5], stream));
-  VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, c.buf[6], stream));
+  VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, true, c.buf[4], stream));
+  VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, true, c.buf[5], stream));
+  VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, false, c.buf[6], stream));
   vorta_attn_io io;
-  io.q = q; io.k = k; io.v = v; io.out = out;
+  io.q = q_att; io.k = k_att; io.v = v; io.out = out;
   io.q_t = io.k_t = io.v_t = nullptr;
   io.o_t = nullptr;
   if (!gather) { io.q_t = c.buf[0]; io.k_t = c.buf[1]; io.v_t = c.buf[2]; io.o_t = c.buf[3]; }
@@ -201,8 +210,17 @@ int vorta_bcs_build_index(vorta_plan* p, const void* feat, int64_t feat_head_str
   return launch_bcs_index(p, rl, ut, keep_idx, assign, stream);
 }
 
+int vorta_rope_apply(vorta_plan* p, const void* src, const uint8_t* routes, void* dst, void* stream) {
+  RouteLists rl;
+  VORTA_TRY(begin(p, routes, &rl));
+  if (!p->rope || rl.count[0] + rl.count[1] == 0) return VORTA_OK;
+  VORTA_TRY(check_ptr(src, "src"));
+  VORTA_TRY(check_ptr(dst, "dst"));
+  return launch_rope_rows(p, rl, src, dst, stream);
+}
+
 int vorta_bcs_pool(vorta_plan* p, const void* src, const uint8_t* routes, const int32_t* keep_idx,
-                   const int32_t* assign, void* dst, void* stream) {
+                   const int32_t* assign, int32_t rotate, void* dst, void* stream) {
   RouteLists rl;
   VORTA_TRY(begin(p, routes, &rl));
   if (!rl.count[2]) return VORTA_OK;
@@ -210,7 +228,7 @@ int vorta_bcs_pool(vorta_plan* p, const void* src, const uint8_t* routes, const 
   VORTA_TRY(check_ptr(keep_idx, "keep_idx"));
   VORTA_TRY(check_ptr(assign, "assign"));
   VORTA_TRY(check_ptr(dst, "dst"));
-  return launch_bcs_pool(p, rl, src, keep_idx, assign, dst, stream);
+  return launch_bcs_pool(p, rl, src, keep_idx, assign, rotate != 0, dst, stream);
 }
 
 int vorta_attention_routed(vorta_plan* p, const uint8_t* routes, const vorta_attn_io* io, void* stream) {
@@ -277,12 +295,27 @@ int vorta_soft_mixture_layer(vorta_plan* p, const void* q, const void* k, const 
     int32_t* keep_idx = (int32_t*)c.buf[8];
     int32_t* assign = (int32_t*)c.buf[9];
     VORTA_TRY(launch_bcs_index(p, rl, user_tensor(p, k), keep_idx, assign, stream));
-    VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, c.buf[4], stream));
-    VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, c.buf[5], stream));
-    VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, c.buf[6], stream));
+    VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, true, c.buf[4], stream));
+    VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, true, c.buf[5], stream));
+    VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, false, c.buf[6], stream));
+    const void *q_att = q, *k_att = k;
+    if (p->rope) {       // rotated copies for the other two branches, behind the core-set buffers
+      size_t core_bytes = 0;
+      VORTA_TRY(vorta_workspace_bytes(p, routes, &core_bytes));
+      const size_t tensor_bytes = ((size_t)p->d.heads * p->N * p->d.head_dim * p->elem_bytes + 255) & ~(size_t)255;
+      char* q_r = (char*)workspace + core_bytes;
+      char* k_r = q_r + tensor_bytes;
+      RouteLists all_full;
+      std::memset(routes, VORTA_ROUTE_FULL, sizeof(routes));
+      VORTA_TRY(split_routes(p, routes, &all_full));
+      VORTA_TRY(launch_rope_rows(p, all_full, q, q_r, stream));
+      VORTA_TRY(launch_rope_rows(p, all_full, k, k_r, stream));
+      q_att = q_r;
+      k_att = k_r;
+    }
     vorta_attn_io io;
     std::memset(&io, 0, sizeof(io));
-    io.q = q; io.k = k; io.v = v; io.out = out;
+    io.q = q_att; io.k = k_att; io.v = v; io.out = out;
     io.q_c = c.buf[4]; io.k_c = c.buf[5]; io.v_c = c.buf[6]; io.o_c = c.buf[7];
     VORTA_TRY(launch_attention_bf16(p, rl, &io, stream));
     std::memset(routes, VORTA_ROUTE_WINDOW, sizeof(routes));

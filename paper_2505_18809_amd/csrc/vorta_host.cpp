@@ -132,6 +132,15 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
   if (bucket_tokens > 64) return fail(VORTA_ESHAPE, "bucket holds %lld tokens, at most 64", (long long)bucket_tokens);
   if (d.keep_num < 1 || d.keep_den < d.keep_num)
     return fail(VORTA_ESHAPE, "core-set ratio %d/%d outside (0, 1]", d.keep_num, d.keep_den);
+  int64_t rope_sum = 0;
+  for (int a = 0; a < 3; ++a) {
+    if (d.rope_dims[a] < 0 || d.rope_dims[a] % 2 || d.rope_dims[a] > d.head_dim)
+      return fail(VORTA_ESHAPE, "rope_dims[%d] = %d: an even channel count in 0..head_dim expected", a, d.rope_dims[a]);
+    rope_sum += d.rope_dims[a];
+  }
+  if (rope_sum > d.head_dim)
+    return fail(VORTA_ESHAPE, "rope_dims add up to %lld channels, the head has %d", (long long)rope_sum, d.head_dim);
+  if (!(d.rope_theta > 0.f)) d.rope_theta = 10000.f;
 
   {
     // the kernels address rows of a head with 32-bit element offsets (row index times row stride)
@@ -236,6 +245,20 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
       }
   p->slot_base[b] = (int32_t)slot;
   p->Lc = slot;
+
+  // rotary embedding table: (cos, sin) of position * theta^(-2 i / span), angles in double
+  p->rope = rope_sum > 0;
+  if (p->rope) {
+    for (int a = 0; a < 3; ++a) {
+      const int span = d.rope_dims[a];
+      for (int pos = 0; pos < grid[a]; ++pos)
+        for (int i = 0; i < span / 2; ++i) {
+          const double angle = (double)pos * std::pow((double)d.rope_theta, -2.0 * i / span);
+          p->rope_cs.push_back((float)std::cos(angle));
+          p->rope_cs.push_back((float)std::sin(angle));
+        }
+    }
+  }
   *out = p;
   return VORTA_OK;
 }
@@ -356,8 +379,8 @@ int vorta_route_select(const float* alpha, int32_t heads, uint8_t* routes) {
   return VORTA_OK;
 }
 
-// Workspace: q_t,k_t,v_t,o_t,q_c,k_c,v_c,o_c,keep_idx,assign, each 256-byte aligned.
-static void workspace_sizes(const vorta_plan* p, const RouteLists& rl, size_t sizes[10]) {
+// Workspace: q_t,k_t,v_t,o_t,q_c,k_c,v_c,o_c,keep_idx,assign,q_r,k_r, each 256-byte aligned.
+static void workspace_sizes(const vorta_plan* p, const RouteLists& rl, size_t sizes[12]) {
   const size_t row = (size_t)p->d.head_dim * p->elem_bytes;
   // tile-ordered copies: only the fp32 layer call makes them (bf16 gathers rows in the window kernel)
   const size_t tiled = p->d.dtype == VORTA_BF16 ? 0 : (size_t)rl.count[1] * p->N * row;
@@ -366,16 +389,20 @@ static void workspace_sizes(const vorta_plan* p, const RouteLists& rl, size_t si
   for (int i = 4; i < 8; ++i) sizes[i] = core;
   sizes[8] = (size_t)rl.count[2] * p->Lc * sizeof(int32_t);
   sizes[9] = (size_t)rl.count[2] * p->L * sizeof(int32_t);
+  // rotated copies of Q and K for the heads on routes 0 and 1: whole tensors in the caller's
+  // layout (rows of the other heads stay unwritten), so that the attention kernels address
+  // them with the strides they use for V and the output
+  sizes[10] = sizes[11] = p->rope && rl.count[0] + rl.count[1] ? (size_t)p->d.heads * p->N * row : 0;
 }
 
-int vorta_workspace_layout(const vorta_plan* p, const uint8_t* routes_host, size_t offsets[10]) {
+int vorta_workspace_layout(const vorta_plan* p, const uint8_t* routes_host, size_t offsets[12]) {
   clear_error();
   if (!offsets) return fail(VORTA_EINVAL, "null offsets");
   RouteLists rl;
   if (int rc = split_routes(p, routes_host, &rl)) return rc;
-  size_t sizes[10], off = 0;
+  size_t sizes[12], off = 0;
   workspace_sizes(p, rl, sizes);
-  for (int i = 0; i < 10; ++i) {
+  for (int i = 0; i < 12; ++i) {
     offsets[i] = off;
     off += (sizes[i] + 255) & ~(size_t)255;
   }
@@ -387,9 +414,9 @@ int vorta_workspace_bytes(const vorta_plan* p, const uint8_t* routes_host, size_
   if (!bytes) return fail(VORTA_EINVAL, "null bytes");
   RouteLists rl;
   if (int rc = split_routes(p, routes_host, &rl)) return rc;
-  size_t sizes[10], off = 0;
+  size_t sizes[12], off = 0;
   workspace_sizes(p, rl, sizes);
-  for (int i = 0; i < 10; ++i) off += (sizes[i] + 255) & ~(size_t)255;
+  for (int i = 0; i < 12; ++i) off += (sizes[i] + 255) & ~(size_t)255;
   *bytes = off + 256;   // never zero, so callers can always allocate it
   return VORTA_OK;
 }
@@ -399,9 +426,12 @@ int vorta_soft_mixture_workspace_bytes(const vorta_plan* p, size_t* bytes) {
   if (!p || !bytes) return fail(VORTA_EINVAL, "null argument");
   uint8_t routes[VORTA_MAX_HEADS];
   if (p->d.dtype == VORTA_BF16) {
-    // fused form: the core-set buffers and index of every head, nothing else
+    // fused form: the core-set buffers and index of every head (and, with a rotary embedding,
+    // the rotated copies of Q and K)
     std::memset(routes, VORTA_ROUTE_CORESET, sizeof(routes));
-    return vorta_workspace_bytes(p, routes, bytes);
+    if (int rc = vorta_workspace_bytes(p, routes, bytes)) return rc;
+    if (p->rope) *bytes += 2 * (((size_t)p->d.heads * p->N * p->d.head_dim * p->elem_bytes + 255) & ~(size_t)255);
+    return VORTA_OK;
   }
   // fp32: the largest single-route workspace + one user-layout output per branch
   size_t most = 0;

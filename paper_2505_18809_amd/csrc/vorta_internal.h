@@ -26,6 +26,10 @@ struct vorta_plan {
   std::vector<int32_t> runs;     // [n_tiles][max_runs][2]
   std::vector<int32_t> n_runs;   // [n_tiles]
   std::vector<int32_t> slot_base;  // [n_buckets + 1]
+  // rotary embedding: (cos, sin) of position * rate for every position of every axis,
+  // [F][pairs_F] then [H][pairs_H] then [W][pairs_W]; empty without rope_dims
+  bool rope = false;
+  std::vector<float> rope_cs;
 
   // device copies of runs / n_runs / slot_base and the tile-order -> sequence-order token table
   // (identity for the text rows), uploaded on first device use
@@ -38,6 +42,7 @@ struct vorta_plan {
   int32_t* d_slot_base = nullptr;
   int32_t* d_tok_of = nullptr;   // [N]
   int32_t* d_tile_row0 = nullptr;   // [n_tiles + 1]
+  float* d_rope_cs = nullptr;
 };
 
 namespace vorta {
@@ -69,7 +74,8 @@ int launch_reorder(vorta_plan* p, const RouteLists& rl, const void* user, void* 
 int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const UserTensor& feat, int32_t* keep_idx,
                      int32_t* assign, void* stream);
 int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const int32_t* keep_idx,
-                    const int32_t* assign, void* dst, void* stream);
+                    const int32_t* assign, bool rotate, void* dst, void* stream);
+int launch_rope_rows(vorta_plan* p, const RouteLists& rl, const void* src, void* dst, void* stream);
 int launch_unpool(vorta_plan* p, const RouteLists& rl, const void* o_c, const int32_t* assign, void* out,
                   void* stream);
 int launch_attention_f32(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream);

@@ -38,6 +38,8 @@ static void release_device_tables(vorta_plan* p) {
     if (*t) (void)hipFree(*t);
     *t = nullptr;
   }
+  if (p->d_rope_cs) (void)hipFree(p->d_rope_cs);
+  p->d_rope_cs = nullptr;
 }
 // vorta_plan_destroy lives with the host code; it frees the device tables through this hook
 static const bool release_hook_set = (g_release_device_tables = release_device_tables, true);
@@ -53,6 +55,8 @@ static int upload_device_tables(vorta_plan* p, int dev) {
   for (int64_t i = 0; i < p->L; ++i) tok_of[perm[i]] = (int32_t)i;
   for (int64_t i = p->L; i < p->N; ++i) tok_of[i] = (int32_t)i;
   if (int rc = upload_table(tok_of, &p->d_tok_of)) return rc;
+  if (p->rope)
+    if (int rc = upload_table(p->rope_cs, &p->d_rope_cs)) return rc;
   int cus = 0;
   VORTA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   if (cus > 0) p->n_cus = cus;
@@ -106,6 +110,47 @@ static Geo make_geo(const vorta_plan* p) {
   g.nbH = p->nb[1]; g.nbW = p->nb[2];
   g.keep_num = p->d.keep_num; g.keep_den = p->d.keep_den;
   return g;
+}
+
+// Rotary embedding: the table holds (cos, sin) per position and channel pair, axis after axis.
+struct Rope {
+  const float2* cs;     // [F][pF], [H][pH], [W][pW]
+  int pF, pH, pW;       // channel pairs that turn with the frame index, the row, the column
+  int baseH, baseW;     // first table entry of the H and W axes
+  int H, W;             // grid extents, to decode a token index
+};
+
+static Rope make_rope(const vorta_plan* p) {
+  Rope r;
+  r.cs = (const float2*)p->d_rope_cs;
+  r.pF = p->d.rope_dims[0] / 2; r.pH = p->d.rope_dims[1] / 2; r.pW = p->d.rope_dims[2] / 2;
+  r.baseH = p->d.F * r.pF;
+  r.baseW = r.baseH + p->d.H * r.pH;
+  r.H = p->d.H; r.W = p->d.W;
+  return r;
+}
+
+// Turns the NP channel pairs x[2i], x[2i+1] that start at channel pair `pair0` of the head,
+// for the video token `tok`.  Pairs past the three spans are left alone.
+template <int NP>
+__device__ __forceinline__ void rope_turn(const Rope& r, int tok, int pair0, double* x) {
+  const int hw = r.H * r.W;
+  const int f = tok / hw, rem = tok - f * hw;
+  const int h = rem / r.W, w = rem - h * r.W;
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    const int j = pair0 + i;
+    int idx = -1;
+    if (j < r.pF) idx = f * r.pF + j;
+    else if (j < r.pF + r.pH) idx = r.baseH + h * r.pH + (j - r.pF);
+    else if (j < r.pF + r.pH + r.pW) idx = r.baseW + w * r.pW + (j - r.pF - r.pH);
+    if (idx >= 0) {
+      const float2 cs = r.cs[idx];
+      const double a = x[2 * i], b = x[2 * i + 1];
+      x[2 * i] = a * (double)cs.x - b * (double)cs.y;
+      x[2 * i + 1] = a * (double)cs.y + b * (double)cs.x;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -371,11 +416,13 @@ int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const UserTensor& ut, 
 // centre and of the tokens pruned into it are summed in fp64, the G partial sums are added
 // across the groups, and group 0 writes the mean to the centre's slot.
 // ------------------------------------------------------------------------------------------
-template <typename T, int D>
+// ROPE: every pooled row is turned by the rotary embedding at the position of the token that owns
+// its slot (the kept token itself; for a merged row the bucket's centre) before it is stored.
+template <typename T, int D, bool ROPE>
 __global__ __launch_bounds__(256) void bcs_pool_kernel(const T* __restrict__ src, HeadList hl, Geo g,
                                                        int n_buckets, long head_stride, long row_stride,
                                                        int n_core_rows, const int* __restrict__ assign,
-                                                       T* __restrict__ dst) {
+                                                       T* __restrict__ dst, Rope rope) {
   constexpr int CN = Chunk<T>::N;           // elements per chunk
   constexpr int CPR = D / CN;               // chunks per row: 16 or 32
   constexpr int G = 64 / CPR;               // token groups per pass
@@ -403,12 +450,20 @@ __global__ __launch_bounds__(256) void bcs_pool_kernel(const T* __restrict__ src
     for (int q = 0; q < G; ++q)
       if (j0 + q < k.size && __shfl(my_slot, min(j0 + q, k.size - 1), 64) == centre_slot) ++members;
     if (j >= k.size) continue;
-    const T* row = base + (long)bucket_token(g, k, j) * row_stride;
+    const int tok = bucket_token(g, k, j);
+    const T* row = base + (long)tok * row_stride;
     if (slot == centre_slot) {
       double x[CN];
       Chunk<T>::load(row, x);
 #pragma unroll
       for (int e = 0; e < CN; ++e) acc[e] += x[e];
+    } else if (ROPE) {
+      double x[CN];
+      Chunk<T>::load(row, x);
+      rope_turn<CN / 2>(rope, tok, c * (CN / 2), x);
+      T* o = out + (long)slot * D;
+#pragma unroll
+      for (int e = 0; e < CN; ++e) Elem<T>::store(o + e, x[e]);
     } else {
       *(uint4*)(out + (long)slot * D) = *(const uint4*)row;
     }
@@ -420,6 +475,7 @@ __global__ __launch_bounds__(256) void bcs_pool_kernel(const T* __restrict__ src
     for (int off = CPR; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
     acc[e] = v / (double)members;
   }
+  if (ROPE) rope_turn<CN / 2>(rope, bucket_token(g, k, k.centre), c * (CN / 2), acc);
   if (grp == 0) {
     T* o = out + (long)centre_slot * D;
 #pragma unroll
@@ -443,7 +499,7 @@ __global__ __launch_bounds__(256) void copy_text_rows_kernel(const uint4* __rest
 }
 
 int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const int32_t* keep_idx,
-                    const int32_t* assign, void* dst, void* stream) {
+                    const int32_t* assign, bool rotate, void* dst, void* stream) {
   (void)keep_idx;   // the slot of every token is in `assign`; kept for a symmetric interface
   if (rl.count[2] == 0) return VORTA_OK;
   const UserTensor ut = user_tensor(p, src);
@@ -452,15 +508,19 @@ int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const 
   const Geo g = make_geo(p);
   const int rows = (int)(p->Lc + p->d.n_text);
   hipStream_t st = (hipStream_t)stream;
-  if (p->d.dtype == VORTA_BF16)
-    hipLaunchKernelGGL((bcs_pool_kernel<uint16_t, 128>), grid, dim3(256), 0, st, (const uint16_t*)src, hl, g,
-                       p->n_buckets, ut.head_stride, ut.row_stride, rows, assign, (uint16_t*)dst);
-  else if (p->d.head_dim == 64)
-    hipLaunchKernelGGL((bcs_pool_kernel<float, 64>), grid, dim3(256), 0, st, (const float*)src, hl, g,
-                       p->n_buckets, ut.head_stride, ut.row_stride, rows, assign, (float*)dst);
-  else
-    hipLaunchKernelGGL((bcs_pool_kernel<float, 128>), grid, dim3(256), 0, st, (const float*)src, hl, g,
-                       p->n_buckets, ut.head_stride, ut.row_stride, rows, assign, (float*)dst);
+  const bool rope_on = rotate && p->rope;
+  const Rope rope = make_rope(p);
+#define VORTA_POOL(T_, D_, R_)                                                                                  \
+  hipLaunchKernelGGL((bcs_pool_kernel<T_, D_, R_>), grid, dim3(256), 0, st, (const T_*)src, hl, g, p->n_buckets, \
+                     ut.head_stride, ut.row_stride, rows, assign, (T_*)dst, rope)
+  if (p->d.dtype == VORTA_BF16) {
+    if (rope_on) VORTA_POOL(uint16_t, 128, true); else VORTA_POOL(uint16_t, 128, false);
+  } else if (p->d.head_dim == 64) {
+    if (rope_on) VORTA_POOL(float, 64, true); else VORTA_POOL(float, 64, false);
+  } else {
+    if (rope_on) VORTA_POOL(float, 128, true); else VORTA_POOL(float, 128, false);
+  }
+#undef VORTA_POOL
   if (int rc = launch_status("bcs_pool_kernel")) return rc;
   if (p->d.n_text > 0) {
     const int cs = chunk_shift(p);
@@ -472,6 +532,56 @@ int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const 
     return launch_status("copy_text_rows_kernel");
   }
   return VORTA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Rotary embedding of whole rows, heads of routes 0 and 1: one thread per (row, 16-byte chunk),
+// looping over the heads; dst has the caller's layout.  Text rows are copied.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rope_rows_kernel(const T* __restrict__ src, T* __restrict__ dst, HeadList hl,
+                                                        int L, int N, long head_stride, long row_stride, int cshift,
+                                                        Rope rope) {
+  constexpr int CN = Chunk<T>::N;
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const int i = (int)(gid >> cshift);
+  const int c = (int)(gid & ((1 << cshift) - 1));
+  if (i >= N) return;
+  const long off0 = (long)i * row_stride + c * CN;
+#pragma unroll 2
+  for (int s = 0; s < hl.n; ++s) {
+    const long off = off0 + hl.id[s] * head_stride;
+    if (i >= L) {
+      *(uint4*)(dst + off) = *(const uint4*)(src + off);
+      continue;
+    }
+    double x[CN];
+    Chunk<T>::load(src + off, x);
+    rope_turn<CN / 2>(rope, i, c * (CN / 2), x);
+#pragma unroll
+    for (int e = 0; e < CN; ++e) Elem<T>::store(dst + off + e, x[e]);
+  }
+}
+
+int launch_rope_rows(vorta_plan* p, const RouteLists& rl, const void* src, void* dst, void* stream) {
+  HeadList hl;
+  hl.n = 0;
+  for (int r = 0; r < 2; ++r)
+    for (int i = 0; i < rl.count[r]; ++i) hl.id[hl.n++] = (uint8_t)rl.heads[r][i];
+  if (hl.n == 0 || !p->rope) return VORTA_OK;
+  const UserTensor ut = user_tensor(p, src);
+  const int cs = chunk_shift(p);
+  const long total = (long)p->N << cs;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  const Rope rope = make_rope(p);
+  hipStream_t st = (hipStream_t)stream;
+  if (p->d.dtype == VORTA_BF16)
+    hipLaunchKernelGGL(rope_rows_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)src, (uint16_t*)dst,
+                       hl, (int)p->L, (int)p->N, ut.head_stride, ut.row_stride, cs, rope);
+  else
+    hipLaunchKernelGGL(rope_rows_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)src, (float*)dst, hl,
+                       (int)p->L, (int)p->N, ut.head_stride, ut.row_stride, cs, rope);
+  return launch_status("rope_rows_kernel");
 }
 
 // ------------------------------------------------------------------------------------------

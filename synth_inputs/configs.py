@@ -30,6 +30,8 @@ class LayerConfig:
     keep_den: int = 2
     route_fractions: Optional[Tuple[float, float, float]] = None   # (full, window, core-set)
     fixed_routes: Optional[Tuple[int, ...]] = None
+    rope_dims: Optional[Tuple[int, int, int]] = None   # channels turned by the F, H, W position; None = no RoPE
+    rope_theta: float = 10000.0
 
     @property
     def n_video(self) -> int:

@@ -8,7 +8,8 @@ from synth_inputs import LayerConfig
 
 def spec_of(cfg: LayerConfig, **over) -> vo.LayerSpec:
     kw = dict(grid=cfg.grid, tile=cfg.tile, window=cfg.window, bucket=cfg.bucket,
-              keep_num=cfg.keep_num, keep_den=cfg.keep_den, n_text=cfg.n_text)
+              keep_num=cfg.keep_num, keep_den=cfg.keep_den, n_text=cfg.n_text,
+              rope_dims=cfg.rope_dims, rope_theta=cfg.rope_theta)
     kw.update(over)
     return vo.LayerSpec(**kw)
 

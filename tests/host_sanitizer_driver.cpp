@@ -53,7 +53,7 @@ static void walk(const vorta_layer_desc& d) {
   int32_t counts[3];
   EXPECT(vorta_route_partition(p, routes.data(), by_route.data(), counts) == VORTA_OK);
   EXPECT(counts[0] + counts[1] + counts[2] == d.heads);
-  size_t bytes = 0, off[10];
+  size_t bytes = 0, off[12];
   EXPECT(vorta_workspace_bytes(p, routes.data(), &bytes) == VORTA_OK && bytes >= 256);
   EXPECT(vorta_workspace_layout(p, routes.data(), off) == VORTA_OK);
   EXPECT(vorta_soft_mixture_workspace_bytes(p, &bytes) == VORTA_OK);
@@ -72,6 +72,9 @@ int main() {
   const int one[3] = {1, 1, 1};
   walk(desc(1, 1, 1, 0, 1, one, one, one, VORTA_CENTER_BLOCK, 1, 1));
   walk(desc(21, 45, 80, 0, 40, (const int[3]){3, 5, 8}, w3, b, VORTA_CENTER_CLAMP, 1, 2));
+  vorta_layer_desc roped = desc(5, 7, 6, 9, 5, t2, w2, b, 0, 1, 2);
+  roped.rope_dims[0] = 44; roped.rope_dims[1] = 42; roped.rope_dims[2] = 42; roped.rope_theta = 0.f;
+  walk(roped);
 
   // rejected descriptions leave no plan behind
   vorta_plan* p = nullptr;

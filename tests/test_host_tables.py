@@ -25,8 +25,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_the_header():
-    # 8 scalars + 3+3 ints + center_mode + 3 ints + 2 ints + float = 21 four-byte fields
-    assert ctypes.sizeof(vorta.binding.vorta_layer_desc) == 21 * 4
+    # 8 scalars + 3+3 ints + center_mode + 3 ints + 2 ints + float + 3 ints + float = 25 four-byte fields
+    assert ctypes.sizeof(vorta.binding.vorta_layer_desc) == 25 * 4
     assert ctypes.sizeof(vorta.binding.vorta_attn_io) == 12 * 8
 
 
@@ -253,6 +253,7 @@ def test_bad_descriptions_are_rejected():
                       (dict(heads=0), -2), (dict(heads=129), -2), (dict(dtype=7), -3), (dict(layout=5), -1),
                       (dict(bucket=(5, 5, 5)), -2), (dict(keep_num=3, keep_den=2), -2),
                       (dict(keep_num=0), -2), (dict(grid=(0, 8, 8)), -2),
+                      (dict(rope_dims=(3, 0, 0)), -2), (dict(rope_dims=(64, 64, 2)), -2), (dict(rope_dims=(-2, 0, 0)), -2),
                       (dict(grid=(512, 256, 256), heads=64, layout=0), -2)):     # 2^25 rows x 8192 elements
         with pytest.raises(vorta.VortaError) as e:
             vorta.vorta_plan_create(**{**ok, **bad})
