@@ -198,8 +198,7 @@ def main():
     if not gather:
         stages["reorder_to_tiles"] = lambda: [vorta.vorta_reorder_to_tiles(plan, s, routes, d) for s, d in ((q, q_t), (k, k_t), (v, v_t))]
     stages.update({
-        "bcs_build_index": lambda: vorta.vorta_bcs_build_index(plan, k, routes, keep_idx, assign),
-        "bcs_pool": lambda: [vorta.vorta_bcs_pool(plan, s, routes, keep_idx, assign, d) for s, d in ((q, q_c), (k, k_c), (v, v_c))],
+        "bcs_select_pool": lambda: vorta.vorta_bcs_select_pool(plan, q, k, v, routes, keep_idx, assign, q_c, k_c, v_c),
         "attention_routed": lambda: vorta.vorta_attention_routed(plan, routes, q=q, k=k, v=v, out=out, q_c=q_c, k_c=k_c,
                                                                   v_c=v_c, o_c=o_c, **tiled),
         "scatter_back": lambda: vorta.vorta_scatter_back(plan, routes, None if gather else o_t, o_c, assign, out),
@@ -221,8 +220,8 @@ def main():
     N, L, Lc = plan.n_tokens, plan.n_video, plan.n_core
     pass_bytes = {
         "reorder_to_tiles": 2 * 3 * n_win * N * row,
-        "bcs_build_index": n_lr * L * row + n_lr * (Lc + L) * 4,
-        "bcs_pool": 3 * n_lr * (N * row + plan.n_core_tokens * row + L * 4),
+        # Q, K, V read once, three pooled tensors and the two index arrays written
+        "bcs_select_pool": 3 * n_lr * (N + plan.n_core_tokens) * row + n_lr * (Lc + L) * 4,
         "scatter_back": (0 if gather else 2 * n_win * N * row) + n_lr * (N + plan.n_core_tokens) * row + n_lr * L * 4,
     }
     attn_ms = stage_ms["attention_routed"]

@@ -227,6 +227,16 @@ int vorta_bcs_build_index(vorta_plan* plan, const void* feat, int64_t feat_head_
 int vorta_bcs_pool(vorta_plan* plan, const void* src, const uint8_t* routes_host,
                    const int32_t* keep_idx, const int32_t* assign, int32_t rotate, void* dst, void* stream);
 
+/* vorta_bcs_build_index on K followed by vorta_bcs_pool of Q, K (rotate = 1) and V, as ONE pass
+ * over the data where the plan allows it (buckets of at most 16 tokens, rows of 256 bytes: the
+ * paper's (2,3,2) bucket in bf16) -- K is then read from memory once and all rows of a bucket are
+ * requested together; otherwise the four separate passes.  The results are those of the separate
+ * calls, bit for bit.  This is the form the layer call runs (section 3.2: selection and merging
+ * are both O(L), appendix complexity paragraph). */
+int vorta_bcs_select_pool(vorta_plan* plan, const void* q, const void* k, const void* v,
+                          const uint8_t* routes_host, int32_t* keep_idx, int32_t* assign, void* q_c, void* k_c,
+                          void* v_c, void* stream);
+
 /* Rotary embedding for the heads on routes 0 and 1: dst rows of those heads = src rows turned
  * at their token's grid position (text rows copied).  src, dst: user layout (dst rows of other
  * heads are not touched); a no-op returning VORTA_OK when the plan has no rope_dims.  The layer

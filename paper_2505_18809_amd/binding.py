@@ -30,7 +30,7 @@ SYMBOLS = [
     "vorta_tile_permutation", "vorta_tile_row0", "vorta_window_boxes", "vorta_window_runs", "vorta_bcs_slot_bases",
     "vorta_plan_upload", "vorta_route_partition", "vorta_router_gates", "vorta_route_select", "vorta_router_device",
     "vorta_reorder_to_tiles", "vorta_reorder_from_tiles",
-    "vorta_bcs_build_index", "vorta_bcs_pool", "vorta_rope_apply", "vorta_attention_routed", "vorta_scatter_back",
+    "vorta_bcs_build_index", "vorta_bcs_pool", "vorta_bcs_select_pool", "vorta_rope_apply", "vorta_attention_routed", "vorta_scatter_back",
     "vorta_workspace_bytes", "vorta_workspace_layout", "vorta_routed_attention_layer",
     "vorta_soft_mixture_workspace_bytes", "vorta_soft_mixture_layer", "vorta_routed_attention_layer_static",
 ]
@@ -379,6 +379,26 @@ def vorta_bcs_build_index(plan: Plan, feat: torch.Tensor, routes, keep_idx=None,
     _check(load_library().vorta_bcs_build_index(plan.handle, _ptr(feat), ctypes.c_int64(feat_head_stride), _u8p(r),
                                                 _ptr(keep_idx), _ptr(assign), _stream(stream)))
     return keep_idx, assign
+
+
+def vorta_bcs_select_pool(plan: Plan, q, k, v, routes, keep_idx=None, assign=None, q_c=None, k_c=None, v_c=None,
+                          stream=None):
+    """Index on K and pooled Q, K, V in one call; returns (keep_idx, assign, q_c, k_c, v_c)."""
+    r = _routes(routes, plan)
+    n = _count(r, 2)
+    dev = q.device
+    if keep_idx is None:
+        keep_idx = torch.empty(n, plan.n_core, dtype=torch.int32, device=dev)
+    if assign is None:
+        assign = torch.empty(n, plan.n_video, dtype=torch.int32, device=dev)
+    q_c, k_c, v_c = (t if t is not None else torch.empty(n, plan.n_core_tokens, plan.head_dim, dtype=plan.torch_dtype, device=dev)
+                     for t in (q_c, k_c, v_c))
+    _check_tensors(plan, q=plan._user(q), k=plan._user(k), v=plan._user(v),
+                   keep_idx=(keep_idx, (n, plan.n_core), torch.int32), assign=(assign, (n, plan.n_video), torch.int32),
+                   q_c=plan._core(q_c, n), k_c=plan._core(k_c, n), v_c=plan._core(v_c, n))
+    _check(load_library().vorta_bcs_select_pool(plan.handle, _ptr(q), _ptr(k), _ptr(v), _u8p(r), _ptr(keep_idx),
+                                                _ptr(assign), _ptr(q_c), _ptr(k_c), _ptr(v_c), _stream(stream)))
+    return keep_idx, assign, q_c, k_c, v_c
 
 
 def vorta_rope_apply(plan: Plan, src: torch.Tensor, routes, dst: torch.Tensor = None, stream=None):

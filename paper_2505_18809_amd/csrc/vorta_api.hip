@@ -125,6 +125,19 @@ static int carve(const vorta_plan* p, const uint8_t* routes, void* workspace, si
   return VORTA_OK;
 }
 
+// Route 2, first half: core-set index on K as given (before any rotation), then Q, K, V pooled;
+// the pooled rows of Q and K are rotated at their slot owner's position.  One fused pass where
+// the bucket is small enough, else the index pass and three pool passes.
+static int select_and_pool(vorta_plan* p, const RouteLists& rl, const void* q, const void* k, const void* v,
+                           int32_t* keep_idx, int32_t* assign, const Carved& c, void* stream) {
+  if (bcs_fused_applies(p))
+    return launch_bcs_select_pool(p, rl, q, k, v, keep_idx, assign, c.buf[4], c.buf[5], c.buf[6], stream);
+  VORTA_TRY(launch_bcs_index(p, rl, user_tensor(p, k), keep_idx, assign, stream));
+  VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, true, c.buf[4], stream));
+  VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, true, c.buf[5], stream));
+  return launch_bcs_pool(p, rl, v, keep_idx, assign, false, c.buf[6], stream);
+}
+
 static int layer(vorta_plan* p, const RouteLists& rl, const void* q, const void* k, const void* v,
                  const uint8_t* routes, void* out, const Carved& c, void* stream) {
   int32_t* keep_idx = (int32_t*)c.buf[8];
@@ -146,12 +159,7 @@ static int layer(vorta_plan* p, const RouteLists& rl, const void* q, const void*
     VORTA_TRY(launch_reorder(p, rl, k_att, c.buf[1], true, stream));
     VORTA_TRY(launch_reorder(p, rl, v, c.buf[2], true, stream));
   }
-  // route 2: core-set index on K as given (before the rotation), then pool Q, K, V; the
-  // pooled rows of Q and K are rotated at their slot owner's position
-  VORTA_TRY(launch_bcs_index(p, rl, user_tensor(p, k), keep_idx, assign, stream));
-  VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, true, c.buf[4], stream));
-  VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, true, c.buf[5], stream));
-  VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, false, c.buf[6], stream));
+  VORTA_TRY(select_and_pool(p, rl, q, k, v, keep_idx, assign, c, stream));
   vorta_attn_io io;
   io.q = q_att; io.k = k_att; io.v = v; io.out = out;
   io.q_t = io.k_t = io.v_t = nullptr;
@@ -208,6 +216,20 @@ int vorta_bcs_build_index(vorta_plan* p, const void* feat, int64_t feat_head_str
     ut.row_stride = p->d.head_dim;
   }
   return launch_bcs_index(p, rl, ut, keep_idx, assign, stream);
+}
+
+int vorta_bcs_select_pool(vorta_plan* p, const void* q, const void* k, const void* v, const uint8_t* routes,
+                          int32_t* keep_idx, int32_t* assign, void* q_c, void* k_c, void* v_c, void* stream) {
+  RouteLists rl;
+  VORTA_TRY(begin(p, routes, &rl));
+  if (!rl.count[2]) return VORTA_OK;
+  VORTA_TRY(check_ptr(q, "q")); VORTA_TRY(check_ptr(k, "k")); VORTA_TRY(check_ptr(v, "v"));
+  VORTA_TRY(check_ptr(keep_idx, "keep_idx")); VORTA_TRY(check_ptr(assign, "assign"));
+  VORTA_TRY(check_ptr(q_c, "q_c")); VORTA_TRY(check_ptr(k_c, "k_c")); VORTA_TRY(check_ptr(v_c, "v_c"));
+  Carved c;
+  std::memset(&c, 0, sizeof(c));
+  c.buf[4] = (char*)q_c; c.buf[5] = (char*)k_c; c.buf[6] = (char*)v_c;
+  return select_and_pool(p, rl, q, k, v, keep_idx, assign, c, stream);
 }
 
 int vorta_rope_apply(vorta_plan* p, const void* src, const uint8_t* routes, void* dst, void* stream) {
@@ -294,10 +316,7 @@ int vorta_soft_mixture_layer(vorta_plan* p, const void* q, const void* k, const 
     VORTA_TRY(carve(p, routes, workspace, workspace_bytes, &c));
     int32_t* keep_idx = (int32_t*)c.buf[8];
     int32_t* assign = (int32_t*)c.buf[9];
-    VORTA_TRY(launch_bcs_index(p, rl, user_tensor(p, k), keep_idx, assign, stream));
-    VORTA_TRY(launch_bcs_pool(p, rl, q, keep_idx, assign, true, c.buf[4], stream));
-    VORTA_TRY(launch_bcs_pool(p, rl, k, keep_idx, assign, true, c.buf[5], stream));
-    VORTA_TRY(launch_bcs_pool(p, rl, v, keep_idx, assign, false, c.buf[6], stream));
+    VORTA_TRY(select_and_pool(p, rl, q, k, v, keep_idx, assign, c, stream));
     const void *q_att = q, *k_att = k;
     if (p->rope) {       // rotated copies for the other two branches, behind the core-set buffers
       size_t core_bytes = 0;

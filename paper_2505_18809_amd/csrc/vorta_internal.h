@@ -75,6 +75,9 @@ int launch_bcs_index(vorta_plan* p, const RouteLists& rl, const UserTensor& feat
                      int32_t* assign, void* stream);
 int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const int32_t* keep_idx,
                     const int32_t* assign, bool rotate, void* dst, void* stream);
+bool bcs_fused_applies(const vorta_plan* p);
+int launch_bcs_select_pool(vorta_plan* p, const RouteLists& rl, const void* q, const void* k, const void* v,
+                           int32_t* keep_idx, int32_t* assign, void* qc, void* kc, void* vc, void* stream);
 int launch_rope_rows(vorta_plan* p, const RouteLists& rl, const void* src, void* dst, void* stream);
 int launch_unpool(vorta_plan* p, const RouteLists& rl, const void* o_c, const int32_t* assign, void* out,
                   void* stream);

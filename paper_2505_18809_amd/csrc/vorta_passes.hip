@@ -134,6 +134,7 @@ static Rope make_rope(const vorta_plan* p) {
 // for the video token `tok`.  Pairs past the three spans are left alone.
 template <int NP>
 __device__ __forceinline__ void rope_turn(const Rope& r, int tok, int pair0, double* x) {
+#pragma clang fp contract(off)
   const int hw = r.H * r.W;
   const int f = tok / hw, rem = tok - f * hw;
   const int h = rem / r.W, w = rem - h * r.W;
@@ -313,12 +314,59 @@ __device__ __forceinline__ double quad_sum(double v) {
 // over the quad.  Then lane j ranks token j.  The products are formed inside fused
 // multiply-adds: a product of two bf16 (or fp32) values is exact in fp64, so fusing changes
 // no bit and halves the fp64 instruction count; everything after the sums stays unfused.
+// Cosine similarity of this quad's token to the bucket's centre from the lane's quarter rows
+// (craw: centre, xraw: token).  nc, the centre's squared norm, is produced when first is set and
+// reused afterwards.  Returns 0 for an invalid lane, a zero norm or a non-finite result.
+template <typename T, int CH>
+__device__ __forceinline__ double quad_similarity(const uint4 (&craw)[CH], const uint4 (&xraw)[CH], bool valid,
+                                                  bool first, double& nc) {
+#pragma clang fp contract(off)
+  double dot = 0.0, nj = 0.0, ncp = 0.0;
+#pragma unroll
+  for (int ch = 0; ch < CH; ++ch) {
+    double c[Chunk<T>::N], x[Chunk<T>::N];
+    Chunk<T>::widen(craw[ch], c);
+    Chunk<T>::widen(xraw[ch], x);
+#pragma unroll
+    for (int e = 0; e < Chunk<T>::N; ++e) {
+      ncp = __builtin_fma(c[e], c[e], ncp);
+      dot = __builtin_fma(c[e], x[e], dot);
+      nj = __builtin_fma(x[e], x[e], nj);
+    }
+  }
+  if (first) nc = quad_sum(ncp);
+  dot = quad_sum(dot);
+  nj = quad_sum(nj);
+  double sim = 0.0;
+  if (valid && nc != 0.0 && nj != 0.0) sim = dot / sqrt(nc * nj);
+  if (!(sim == sim)) sim = 0.0;       // non-finite features: keep the ranking a total order
+  return sim;
+}
+
+// Lane j holds the similarity of token j.  Ranks the non-centre tokens (larger similarity first,
+// ties by index), prunes the first k.prune of them and numbers the kept tokens in raster order.
+// Returns the slot token `lane` reads its output from (its own if kept, else the centre's);
+// kept / own_slot say whether the lane's token owns a slot and which.
+__device__ __forceinline__ int rank_and_assign(const Bucket& k, int lane, double my_sim, int base_slot, bool& kept,
+                                               int& centre_slot) {
+  int rank = 0;
+  for (int m = 0; m < k.size; ++m) {
+    const double sm = __shfl(my_sim, m, 64);
+    if (m != k.centre && (sm > my_sim || (sm == my_sim && m < lane))) ++rank;
+  }
+  const bool in_bucket = lane < k.size;
+  kept = in_bucket && (lane == k.centre || rank >= k.prune);
+  const unsigned long long kept_mask = __ballot(kept);
+  const int my_slot = base_slot + __popcll(kept_mask & ((1ull << lane) - 1ull));
+  centre_slot = base_slot + __popcll(kept_mask & ((1ull << k.centre) - 1ull));
+  return kept ? my_slot : centre_slot;
+}
+
 template <typename T, int D>   // D = head_dim
 __global__ __launch_bounds__(256) void bcs_index_kernel(const T* __restrict__ feat, HeadList hl, Geo g,
                                                         int n_buckets, const int* __restrict__ slot_base,
                                                         long head_stride, long row_stride, int Lc,
                                                         int* __restrict__ keep_idx, int* __restrict__ assign) {
-#pragma clang fp contract(off)
   constexpr int EP = D / 4;                 // elements per lane
   constexpr int CH = EP / Chunk<T>::N;      // 16-byte chunks per lane
   const int lane = threadIdx.x & 63;
@@ -346,46 +394,19 @@ __global__ __launch_bounds__(256) void bcs_index_kernel(const T* __restrict__ fe
     uint4 xraw[CH];
 #pragma unroll
     for (int ch = 0; ch < CH; ++ch) xraw[ch] = Chunk<T>::raw(row + ch * Chunk<T>::N);
-    double dot = 0.0, nj = 0.0, ncp = 0.0;
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-      double c[Chunk<T>::N], x[Chunk<T>::N];
-      Chunk<T>::widen(craw[ch], c);
-      Chunk<T>::widen(xraw[ch], x);
-#pragma unroll
-      for (int e = 0; e < Chunk<T>::N; ++e) {
-        ncp = __builtin_fma(c[e], c[e], ncp);
-        dot = __builtin_fma(c[e], x[e], dot);
-        nj = __builtin_fma(x[e], x[e], nj);
-      }
-    }
-    if (pass == 0) nc = quad_sum(ncp);
-    dot = quad_sum(dot);
-    nj = quad_sum(nj);
-    double sim = 0.0;
-    if (valid && nc != 0.0 && nj != 0.0) sim = dot / sqrt(nc * nj);
-    if (!(sim == sim)) sim = 0.0;       // non-finite features: keep the ranking a total order
+    const double sim = quad_similarity<T, CH>(craw, xraw, valid, pass == 0, nc);
     // token 16 pass + t sits in lanes 4t .. 4t+3; hand it to lane 16 pass + t
     const double mine = __shfl(sim, 4 * (lane & 15), 64);
     if ((lane >> 4) == pass) my_sim = mine;
   }
 
-  // rank of token `lane` among the non-centre tokens: larger similarity first, ties by index
-  int rank = 0;
-  for (int m = 0; m < k.size; ++m) {
-    const double sm = __shfl(my_sim, m, 64);
-    if (m != k.centre && (sm > my_sim || (sm == my_sim && m < lane))) ++rank;
-  }
-  const bool in_bucket = lane < k.size;
-  const bool kept = in_bucket && (lane == k.centre || rank >= k.prune);
-  const unsigned long long kept_mask = __ballot(kept);
-  const int base_slot = slot_base[b];
-  const int my_slot = base_slot + __popcll(kept_mask & ((1ull << lane) - 1ull));
-  const int centre_slot = base_slot + __popcll(kept_mask & ((1ull << k.centre) - 1ull));
-  if (in_bucket) {
+  bool kept;
+  int centre_slot;
+  const int slot = rank_and_assign(k, lane, my_sim, slot_base[b], kept, centre_slot);
+  if (lane < k.size) {
     const int tok = bucket_token(g, k, lane);
-    if (kept) keep_idx[(long)s * Lc + my_slot] = tok;
-    assign[(long)s * g.L + tok] = kept ? my_slot : centre_slot;
+    if (kept) keep_idx[(long)s * Lc + slot] = tok;
+    assign[(long)s * g.L + tok] = slot;
   }
 }
 
@@ -529,6 +550,168 @@ int launch_bcs_pool(vorta_plan* p, const RouteLists& rl, const void* src, const 
     hipLaunchKernelGGL(copy_text_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        (const uint4*)src, (uint4*)dst, hl, (int)p->L, p->d.n_text, (int)p->Lc,
                        ut.head_stride / epc, ut.row_stride / epc, cs);
+    return launch_status("copy_text_rows_kernel");
+  }
+  return VORTA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Select and pool in one pass (what the layer call runs when a bucket holds at most 16 tokens and
+// a row is 16 chunks, which covers the paper's (2,3,2) bucket in bf16): one wavefront per (bucket,
+// head) requests, before it computes anything, the bucket's K rows in the index kernel's form (a
+// quarter row per lane) and its Q, K and V rows in the pool kernel's form (chunk c of tokens grp,
+// grp + 4, ...), so one memory round trip covers them all and K comes from HBM once; then it
+// ranks exactly as bcs_index_kernel does, writes keep_idx / assign, and merges and stores the
+// three tensors exactly as bcs_pool_kernel does (same operations in the same order: the results
+// of the two forms are identical bit for bit).
+// ------------------------------------------------------------------------------------------
+template <typename T, int D, bool ROPE>
+__global__ __launch_bounds__(256) void bcs_select_pool_kernel(const T* __restrict__ q, const T* __restrict__ k,
+                                                              const T* __restrict__ v, HeadList hl, Geo g, int n_buckets,
+                                                              const int* __restrict__ slot_base, long head_stride,
+                                                              long row_stride, int Lc, int n_core_rows,
+                                                              int* __restrict__ keep_idx, int* __restrict__ assign,
+                                                              T* __restrict__ qc, T* __restrict__ kc, T* __restrict__ vc,
+                                                              Rope rope) {
+  constexpr int CN = Chunk<T>::N;
+  static_assert(D / CN == 16, "rows of 16 chunks");
+  constexpr int EP = D / 4, CH = EP / CN;   // index form: elements and chunks per lane
+  constexpr int G = 4, P = 4;               // pool form: token groups per pass, passes for up to 16 tokens
+  const int lane = threadIdx.x & 63;
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int s = blockIdx.y;
+  if (b >= n_buckets) return;
+  const Bucket kb = bucket_of(g, b);        // kb.size <= 16: checked on the host
+  const long head_off = hl.id[s] * head_stride;
+
+  // ---- every load of the wavefront
+  const int quarter = lane & 3, tl = lane >> 2;
+  const bool valid = tl < kb.size && tl != kb.centre;
+  uint4 craw[CH], xraw[CH];
+  {
+    const T* crow = k + head_off + (long)bucket_token(g, kb, kb.centre) * row_stride + quarter * EP;
+    const T* xrow = k + head_off + (long)bucket_token(g, kb, valid ? tl : kb.centre) * row_stride + quarter * EP;
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+      craw[ch] = Chunk<T>::raw(crow + ch * CN);
+      xraw[ch] = Chunk<T>::raw(xrow + ch * CN);
+    }
+  }
+  const int c = lane & 15, grp = lane >> 4;
+  uint4 rq[P], rk[P], rv[P];
+  int tok_p[P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    tok_p[p] = bucket_token(g, kb, min(G * p + grp, kb.size - 1));
+    const long off = head_off + (long)tok_p[p] * row_stride + c * CN;
+    rq[p] = Chunk<T>::raw(q + off);
+    rk[p] = Chunk<T>::raw(k + off);
+    rv[p] = Chunk<T>::raw(v + off);
+  }
+
+  // ---- select
+  double nc = 0.0;
+  const double sim = quad_similarity<T, CH>(craw, xraw, valid, true, nc);
+  const double mine = __shfl(sim, 4 * (lane & 15), 64);
+  const double my_sim = lane < 16 ? mine : 0.0;
+  bool kept;
+  int centre_slot;
+  const int slot_of_lane = rank_and_assign(kb, lane, my_sim, slot_base[b], kept, centre_slot);
+  if (lane < kb.size) {
+    const int tok = bucket_token(g, kb, lane);
+    if (kept) keep_idx[(long)s * Lc + slot_of_lane] = tok;
+    assign[(long)s * g.L + tok] = slot_of_lane;
+  }
+
+  // ---- pool
+  const int centre_tok = bucket_token(g, kb, kb.centre);
+  const int members = kb.prune + 1;
+  int slot_p[P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) slot_p[p] = __shfl(slot_of_lane, min(G * p + grp, kb.size - 1), 64);
+  auto pool = [&](const uint4 (&rows)[P], T* dst, bool rotate) {
+    T* out = dst + (long)s * n_core_rows * D + c * CN;
+    double acc[CN];
+#pragma unroll
+    for (int e = 0; e < CN; ++e) acc[e] = 0.0;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      if (G * p + grp >= kb.size) continue;
+      if (slot_p[p] == centre_slot) {
+        double x[CN];
+        Chunk<T>::widen(rows[p], x);
+#pragma unroll
+        for (int e = 0; e < CN; ++e) acc[e] += x[e];
+      } else if (rotate) {
+        double x[CN];
+        Chunk<T>::widen(rows[p], x);
+        rope_turn<CN / 2>(rope, tok_p[p], c * (CN / 2), x);
+        T* o = out + (long)slot_p[p] * D;
+#pragma unroll
+        for (int e = 0; e < CN; ++e) Elem<T>::store(o + e, x[e]);
+      } else {
+        *(uint4*)(out + (long)slot_p[p] * D) = rows[p];
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < CN; ++e) {
+      double sum = acc[e];
+      sum += __shfl_xor(sum, 16, 64);
+      sum += __shfl_xor(sum, 32, 64);
+      acc[e] = sum / (double)members;
+    }
+    if (rotate) rope_turn<CN / 2>(rope, centre_tok, c * (CN / 2), acc);
+    if (grp == 0) {
+      T* o = out + (long)centre_slot * D;
+#pragma unroll
+      for (int e = 0; e < CN; ++e) Elem<T>::store(o + e, acc[e]);
+    }
+  };
+  pool(rq, qc, ROPE);
+  pool(rk, kc, ROPE);
+  pool(rv, vc, false);
+}
+
+// True when the fused form applies: buckets of at most 16 tokens, rows of 16 chunks.
+bool bcs_fused_applies(const vorta_plan* p) {
+  const long bucket_tokens = (long)p->d.bucket[0] * p->d.bucket[1] * p->d.bucket[2];
+  const int chunks = p->d.head_dim * p->elem_bytes / 16;
+  return bucket_tokens <= 16 && chunks == 16;
+}
+
+// Index on K, then Q, K, V pooled (Q and K rotated if the plan has a rotary embedding) into
+// qc, kc, vc, and the text rows copied behind them.
+int launch_bcs_select_pool(vorta_plan* p, const RouteLists& rl, const void* q, const void* k, const void* v,
+                           int32_t* keep_idx, int32_t* assign, void* qc, void* kc, void* vc, void* stream) {
+  if (rl.count[2] == 0) return VORTA_OK;
+  const UserTensor ut = user_tensor(p, k);
+  const dim3 grid((p->n_buckets + 3) / 4, rl.count[2]);
+  const HeadList hl = head_list(rl, 2);
+  const Geo g = make_geo(p);
+  const int rows = (int)(p->Lc + p->d.n_text);
+  const Rope rope = make_rope(p);
+  hipStream_t st = (hipStream_t)stream;
+#define VORTA_FUSED(T_, D_, R_)                                                                                        \
+  hipLaunchKernelGGL((bcs_select_pool_kernel<T_, D_, R_>), grid, dim3(256), 0, st, (const T_*)q, (const T_*)k,         \
+                     (const T_*)v, hl, g, p->n_buckets, p->d_slot_base, ut.head_stride, ut.row_stride, (int)p->Lc, rows, \
+                     keep_idx, assign, (T_*)qc, (T_*)kc, (T_*)vc, rope)
+  if (p->d.dtype == VORTA_BF16) {
+    if (p->rope) VORTA_FUSED(uint16_t, 128, true); else VORTA_FUSED(uint16_t, 128, false);
+  } else {
+    if (p->rope) VORTA_FUSED(float, 64, true); else VORTA_FUSED(float, 64, false);
+  }
+#undef VORTA_FUSED
+  if (int rc = launch_status("bcs_select_pool_kernel")) return rc;
+  if (p->d.n_text > 0) {
+    const int cs = chunk_shift(p);
+    const int epc = 16 / p->elem_bytes;
+    const long total = (long)p->d.n_text << cs;
+    const void* srcs[3] = {q, k, v};
+    void* dsts[3] = {qc, kc, vc};
+    for (int t = 0; t < 3; ++t)
+      hipLaunchKernelGGL(copy_text_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                         (const uint4*)srcs[t], (uint4*)dsts[t], hl, (int)p->L, p->d.n_text, (int)p->Lc,
+                         ut.head_stride / epc, ut.row_stride / epc, cs);
     return launch_status("copy_text_rows_kernel");
   }
   return VORTA_OK;

@@ -99,3 +99,20 @@ def test_soft_mixture_with_rope(dtype, d, rope):
     err = np.abs(f64(out) - want).max()
     say(f"soft mixture with rope {dtype}: max-abs {err:.3e}")
     assert err <= TOL[dtype]
+
+
+def test_layer_with_rope_equals_its_staged_calls():
+    """rope rows -> index -> rotating pool -> attention -> scatter back, call by call, against
+    the one-call layer: the same kernels on the same buffers, so equal bit for bit."""
+    cfg = roped_cfg("rope_staged", (6, 8, 8), 5, "bf16", (2, 4, 4), [0, 1, 2, 2, 1], n_text=10)
+    routes = np.array(cfg.fixed_routes, dtype=np.uint8)
+    q, k, v = make_qkv(cfg, DEV)
+    plan = vorta.plan_for(cfg)
+    out = vorta.vorta_routed_attention_layer(plan, q, k, v, routes)
+    q_r, k_r = vorta.vorta_rope_apply(plan, q, routes), vorta.vorta_rope_apply(plan, k, routes)
+    keep_idx, assign, q_c, k_c, v_c = vorta.vorta_bcs_select_pool(plan, q, k, v, routes)
+    o_c, staged = torch.empty_like(q_c), torch.zeros_like(q)
+    vorta.vorta_attention_routed(plan, routes, q=q_r, k=k_r, v=v, out=staged, q_c=q_c, k_c=k_c, v_c=v_c, o_c=o_c)
+    vorta.vorta_scatter_back(plan, routes, None, o_c, assign, staged)
+    torch.cuda.synchronize()
+    assert torch.equal(out, staged)

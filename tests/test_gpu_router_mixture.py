@@ -227,3 +227,38 @@ def test_core_set_index_on_a_feature_shared_by_all_heads(dtype, d):
     assert np.array_equal(keep_idx[0].cpu().numpy(), own)
     with pytest.raises(vorta.VortaError):
         vorta.vorta_bcs_build_index(plan, per_head, routes, feat_head_stride=L * d - 8)      # heads would overlap
+
+
+# ------------------------------------------------------------------ fused select + pool --
+
+@pytest.mark.parametrize("name,grid,bucket,num,den,dtype,d,rope", [
+    ("paper_bucket", (5, 7, 9), (2, 3, 2), 1, 2, "bf16", 128, None),          # clipped buckets of 1..12 tokens
+    ("sixteen", (4, 8, 8), (2, 2, 4), 1, 4, "bf16", 128, None),               # the largest bucket the fused form takes
+    ("fp32", (4, 6, 8), (2, 3, 2), 2, 3, "fp32", 64, None),
+    ("rope", (5, 7, 9), (2, 3, 2), 1, 2, "bf16", 128, (44, 42, 42)),
+    ("rope_fp32", (4, 6, 8), (1, 4, 4), 1, 2, "fp32", 64, (16, 24, 24)),
+    ("separate_passes", (4, 6, 9), (3, 3, 3), 1, 2, "bf16", 128, (44, 42, 42)),  # 27 tokens: not fused, same entry point
+    ("fp32_d128", (4, 6, 8), (2, 3, 2), 1, 2, "fp32", 128, None),             # rows of 32 chunks: not fused
+])
+def test_select_and_pool_in_one_pass_equals_the_separate_passes(name, grid, bucket, num, den, dtype, d, rope):
+    """vorta_bcs_select_pool against vorta_bcs_build_index + 3 x vorta_bcs_pool: identical index
+    arrays and pooled tensors, bit for bit, and the index arrays equal to the oracle's."""
+    cfg = LayerConfig(name, grid, 4, d, dtype, (1, 1, 1), (1, 1, 1), seed=53, n_text=7, fixed_routes=(2, 0, 2, 2),
+                      bucket=bucket, keep_num=num, keep_den=den, rope_dims=rope)
+    for layout in (1, 0):
+        q, k, v = make_qkv(cfg, DEV, layout)
+        plan = vorta.plan_for(cfg, layout=layout)
+        routes = np.array(cfg.fixed_routes, dtype=np.uint8)
+        keep_idx, assign = vorta.vorta_bcs_build_index(plan, k, routes)
+        q_c = vorta.vorta_bcs_pool(plan, q, routes, keep_idx, assign, rotate=True)
+        k_c = vorta.vorta_bcs_pool(plan, k, routes, keep_idx, assign, rotate=True)
+        v_c = vorta.vorta_bcs_pool(plan, v, routes, keep_idx, assign, rotate=False)
+        got = vorta.vorta_bcs_select_pool(plan, q, k, v, routes)
+        torch.cuda.synchronize()
+        for want, have, what in zip((keep_idx, assign, q_c, k_c, v_c), got, ("keep_idx", "assign", "q_c", "k_c", "v_c")):
+            assert torch.equal(want, have), f"{name} layout {layout}: {what}"
+        kh = hnd(k, layout)
+        for slot, h in enumerate([0, 2, 3]):
+            ki, asg, gap = vo.bcs_select(f64(kh[h])[:cfg.n_video], grid, bucket, num, den)
+            assert gap > 1e-9
+            assert np.array_equal(got[0][slot].cpu().numpy(), ki) and np.array_equal(got[1][slot].cpu().numpy(), asg)
