@@ -574,16 +574,28 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
       flen = run_len(fr);
     }
   };
+  // The lookups are loads the compiler does not see either (it would wait for them with
+  // vmcnt(0), which also drains the row loads requested after them): they are requested BEFORE
+  // the row loads of their iteration, so that win_wait -- everything but the last four vector
+  // memory operations complete -- returns as soon as the indices are there, whatever the row
+  // loads behind them are doing (the counter retires in order).
   auto win_idx = [&]() {           // token indices of the noted block
     int rows[2];
     block_rows<2>(rl, wi_run, wi_pos, wi_start, wi_len, KB, ld_row, STG_STEP, rows);
-    gi0 = a.tok_of[rows[0]];
-    gi1 = a.tok_of[rows[1]];
+    asm volatile("global_load_dword %0, %2, %4\n\tglobal_load_dword %1, %3, %4"
+                 : "=&v"(gi0), "=&v"(gi1)
+                 : "v"(rows[0] * 4), "v"(rows[1] * 4), "s"(a.tok_of)
+                 : "memory");
+  };
+  auto win_wait = [&](bool rows_behind) {   // indices usable; rows_behind: four row loads were requested after them
+    if (rows_behind) asm volatile("s_waitcnt vmcnt(4)" : "+v"(gi0), "+v"(gi1)::"memory");
+    else asm volatile("s_waitcnt vmcnt(0)" : "+v"(gi0), "+v"(gi1)::"memory");
   };
   auto win_off = [&](int gi) { return __umul24((unsigned)gi, row_stride) + (unsigned)ld_col; };
-  auto fetch_all = [&](int b) {    // rows of the block under the cursor, block b, into its ring stages
+  auto fetch_all = [&](int b, bool first = false) {   // rows of the block under the cursor, block b, into its ring stages
     unsigned o0_, o1_;
     if constexpr (WIN) {
+      win_wait(!first);
       o0_ = win_off(gi0);
       o1_ = win_off(gi1);
       win_at();
@@ -620,7 +632,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
     win_at();
     win_idx();
   }
-  fetch_all(0);                    // blocks 0, 1 and 2 into their stages; iteration i requests block i+3
+  fetch_all(0, true);              // blocks 0, 1 and 2 into their stages; iteration i requests block i+3
   fetch_all(1);
   fetch_all(2);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -749,15 +761,14 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
         else ps0 += ex[n - 2];
       }
       // ---- staging: the rows of block i+3 are requested -- addresses in slot SO, the four loads
-      // from slot SL + 1 on, SP slots apart -- and (WIN) the token indices of block i+4 looked up
-      // in slot SI.  32 slots: the loads are spread over the iteration, and the lookup comes
-      // right after the addresses, which were the last use of the indices it replaces, so that
-      // it has almost a whole iteration to return (window launch of 432-token tiles -3 %
-      // against loads packed into slots 23..26 and the lookup in slot 27).  16 slots: placement
-      // made no difference; loads packed late, lookup after them.
+      // from slot SL + 1 on, SP slots apart (32 slots: spread over the iteration; 16 slots: in
+      // a row) -- and (WIN) the token indices of block i+4 looked up in slot SI, right after the
+      // addresses, which were the last use of the indices they replace, and ahead of the row
+      // loads, so that waiting for them a whole iteration later does not wait for those.
       constexpr int SL = NS == 32 ? 8 : 9, SP = NS == 32 ? 4 : 1;
-      constexpr int SO = NS == 32 ? (WIN ? 1 : SL) : SL, SI = NS == 32 ? 2 : 14;
+      constexpr int SO = WIN ? 1 : SL, SI = 2;
       if (n == SO) {
+        if constexpr (WIN) win_wait(true);
         off0 = WIN ? win_off(gi0) : row_off(0);
         off1 = WIN ? win_off(gi1) : row_off(1);
       }
