@@ -327,9 +327,8 @@ def test_row_maxima_that_jump_or_creep_late_in_the_key_stream(tile):
     for h in range(cfg.heads):
         r = cfg.fixed_routes[h]
         kh = k[h].float()
-        # scores creep up (or down) along the keys; gentler on the core-set heads, whose pooled
-        # rows are rounded to bf16 (the 2e-2 bar assumes inputs of about unit variance)
-        kh = kh + (6.0 if r == 2 else 24.0) * ramp * u[None, :]
+        # scores creep up (or down) along the keys, by up to 60 / sqrt(d) = 5.3 per unit of <q, u>
+        kh = kh + 60.0 * ramp * u[None, :]
         late = ((int(0.45 * N), 100), (int(0.93 * N), 2000), (N - 1, 7))
         if r == 1:
             late = tuple((int(last_window_token(row, back)), row) for back, row in ((0, 100), (5, 2000), (40, 7)))
@@ -341,9 +340,16 @@ def test_row_maxima_that_jump_or_creep_late_in_the_key_stream(tile):
     spec = spec_of(cfg)
     for h, r in enumerate(routes):
         want = vo.head_attention(int(r), f64(q[h]), f64(k[h]), f64(v[h]), spec, None)
-        err = np.abs(f64(out[h]) - want).max()
-        say(f"late_max {tile} head {h} route {r}: max-abs {err:.3e}")
-        assert err <= TOL["bf16"], f"head {h} route {r}: max-abs {err:.3e}"
+        err = np.abs(f64(out[h]) - want)
+        # A row that one key dominates outright returns that key's value row, and with unit-variance
+        # V some of its 128 entries exceed 4, where half a bf16 ulp is already 1.6e-2: the 2e-2 bar
+        # (derived for |O| of about 2 and less) is held wherever |O| <= 2.5 and widened in
+        # proportion beyond, to 2^-7 |O| (output rounding 2^-8 |O| + rounding of P 2^-9 |O|, and margin).
+        bar = np.maximum(TOL["bf16"], 2.0 ** -7 * np.abs(want))
+        say(f"late_max {tile} head {h} route {r}: max-abs {err.max():.3e} (largest |O| {np.abs(want).max():.2f}, "
+            f"entries over 2e-2: {(err > TOL['bf16']).sum()})")
+        assert (err <= bar).all(), f"head {h} route {r}: max-abs {err.max():.3e}"
+        assert (err > TOL["bf16"]).sum() <= 8                 # and those entries are a handful
 
 
 def test_layer_equals_the_staged_calls_and_is_deterministic():
