@@ -156,6 +156,16 @@ int vorta_window_boxes(const vorta_plan* plan, int32_t* boxes);
  * runs: host int32[n_tiles][max_runs][2]; n_runs: host int32[n_tiles]. */
 int vorta_window_runs(const vorta_plan* plan, int32_t* runs, int32_t* n_runs);
 
+/* How the bf16 layer call cuts the work of route 1 (tiles of at most 128 tokens): query tiles
+ * whose runs are identical see the same keys (Algorithm 1: under the clamped centre rule a border
+ * tile and its inner neighbour on every axis, under the block rule all tiles of a block) and are
+ * computed together, up to three tiles and 256 rows per work item.  items: host
+ * int32[counts[0] + counts[1]][4] = {tile, tile, tile, n_tiles_in_item}, first the counts[0] items
+ * of more than 128 rows, then the counts[1] items of at most 128 rows; every tile appears in
+ * exactly one item.  items may be NULL to query the counts.  Both counts are 0 when a tile holds
+ * more than 128 tokens (such tiles are cut into 256-row query blocks instead). */
+int vorta_window_items(const vorta_plan* plan, int32_t* items, int32_t counts[2]);
+
 /* BCS slot layout (section 3.2): buckets in raster order of bucket coordinates; bucket b owns
  * core-set slots [slot_base[b], slot_base[b+1]).  slot_base: host int32[n_buckets + 1]. */
 int vorta_bcs_slot_bases(const vorta_plan* plan, int32_t* slot_base);

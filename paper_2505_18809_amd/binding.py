@@ -27,7 +27,8 @@ VORTA_STATIC_SCRATCH_BYTES = 32 << 20
 
 SYMBOLS = [
     "vorta_strerror", "vorta_last_error", "vorta_plan_create", "vorta_plan_destroy", "vorta_plan_info_get",
-    "vorta_tile_permutation", "vorta_tile_row0", "vorta_window_boxes", "vorta_window_runs", "vorta_bcs_slot_bases",
+    "vorta_tile_permutation", "vorta_tile_row0", "vorta_window_boxes", "vorta_window_runs", "vorta_window_items",
+    "vorta_bcs_slot_bases",
     "vorta_plan_upload", "vorta_route_partition", "vorta_router_gates", "vorta_route_select", "vorta_router_device",
     "vorta_reorder_to_tiles", "vorta_reorder_from_tiles",
     "vorta_bcs_build_index", "vorta_bcs_pool", "vorta_bcs_select_pool", "vorta_rope_apply", "vorta_attention_routed", "vorta_scatter_back",
@@ -254,6 +255,16 @@ def vorta_window_runs(plan: Plan):
     n_runs = np.empty(plan.n_tiles, dtype=np.int32)
     _check(load_library().vorta_window_runs(plan.handle, _i32p(runs), _i32p(n_runs)))
     return runs, n_runs
+
+
+def vorta_window_items(plan: Plan):
+    """(items of more than 128 rows, items of at most 128 rows), each int32 [n, 4] = tile, tile, tile, count."""
+    counts = np.zeros(2, dtype=np.int32)
+    _check(load_library().vorta_window_items(plan.handle, None, _i32p(counts)))
+    items = np.zeros((int(counts.sum()), 4), dtype=np.int32)
+    if len(items):
+        _check(load_library().vorta_window_items(plan.handle, _i32p(items), _i32p(counts)))
+    return items[:counts[0]], items[counts[0]:]
 
 
 def vorta_bcs_slot_bases(plan: Plan) -> np.ndarray:

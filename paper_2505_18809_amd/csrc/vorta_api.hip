@@ -50,7 +50,8 @@ static int begin(vorta_plan* p, const uint8_t* routes, RouteLists* rl) {
   return ensure_device_tables(p);
 }
 
-int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, int win_part, AttnArgs* a) {
+int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, int win_part, AttnArgs* a,
+                   int win_list) {
   std::memset(a, 0, sizeof(*a));
   const UserTensor ut = user_tensor(p, io->q);
   a->q0 = io->q; a->k0 = io->k; a->v0 = io->v; a->o0 = io->out;
@@ -77,7 +78,14 @@ int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io,
   const long end_text = win_part & WIN_TEXT ? (long)rl.count[1] * a->qb_text : 0;
   const long end_dense = end_text + (long)rl.count[0] * a->qb_dense;
   const long end_core = end_dense + (long)rl.count[2] * a->qb_core;
-  const long end_tile = end_core + (win_part & WIN_TILES ? (long)rl.count[1] * a->n_tiles * a->qb_tile : 0);
+  long tile_items = (long)a->n_tiles * a->qb_tile;        // per window head
+  if (win_list >= 0) {
+    a->win_items = p->d_win_items;
+    a->win_first = win_list == 0 ? 0 : p->n_win_big;
+    a->win_count = win_list == 0 ? p->n_win_big : p->n_win_small;
+    tile_items = a->win_count;
+  }
+  const long end_tile = end_core + (win_part & WIN_TILES ? (long)rl.count[1] * tile_items : 0);
   if (end_tile > 0x7fffffffL) return fail(VORTA_ESHAPE, "%ld work items exceed the grid limit", end_tile);
   a->end_text = (int)end_text;
   a->end_dense = (int)end_dense;

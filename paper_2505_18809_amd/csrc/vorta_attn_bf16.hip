@@ -161,7 +161,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   // Q^T fragments: lane = query (l32), 8 consecutive dims per 16-wide k slice
   bf16x8 qf[8];
   {
-    const unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    const unsigned qrow = w.row(min(32 * wave + l32, w.n_rows - 1));
     const uint16_t* qp = Q + qrow * row_stride + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qp + 16 * ks));
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(64 * NW, 8 / NW) void attn_bf16_kernel(const AttnAr
   for (int i = 0; i < 8; ++i) {
     const int row = (lane >> 4) + 4 * i;
     if (32 * wave + row < w.n_rows)
-      *(uint4*)(O + (unsigned)(w.row0 + 32 * wave + row) * row_stride + (lane & 15) * 8) =
+      *(uint4*)(O + (unsigned)w.row(32 * wave + row) * row_stride + (lane & 15) * 8) =
           *(const uint4*)(st + row * LSTR + (lane & 15) * 8);
   }
 }
@@ -497,7 +497,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
 
   bf16x8 qf[8];
   {
-    unsigned qrow = w.row0 + min(32 * wave + l32, w.n_rows - 1);
+    unsigned qrow = w.row(min(32 * wave + l32, w.n_rows - 1));
     if (WIN) qrow = (unsigned)a.tok_of[qrow];
     const uint16_t* qp = Q + qrow * row_stride + 8 * g;
 #pragma unroll
@@ -874,7 +874,7 @@ __global__ __launch_bounds__(64 * NWV, 8 / NWV) void attn_bf16_pipe_kernel(const
   unsigned orow[8];                // looked up together, ahead of the barrier
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    orow[i] = w.row0 + min(32 * wave + (lane >> 4) + 4 * i, w.n_rows - 1);
+    orow[i] = w.row(min(32 * wave + (lane >> 4) + 4 * i, w.n_rows - 1));
     if (WIN) orow[i] = (unsigned)a.tok_of[orow[i]];
   }
   STORE_TILE(0, o[0]) STORE_TILE(1, o[1]) STORE_TILE(2, o[2]) STORE_TILE(3, o[3])
@@ -951,15 +951,29 @@ int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_
   // wavefronts, smaller tiles in 128-row workgroups of 4 wavefronts on 32-key blocks, two per CU.
   // Over tile-ordered copies: the plain 128-row kernel.
   const bool win_long = a.win_gather && p->tile_tokens > BM;
-  if (int rc = fill_attn_args(p, win_rl, io, win_long ? BM_LONG : BM, WIN_TILES, &a)) return rc;
-  if (a.end_tile > 0 && win_long) {
-    const int n_split = std::min(a.end_tile, p->n_cus / 2);
-    a.split_from = a.end_tile - n_split;
-    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 8>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a, NoMix());
-  } else if (a.end_tile > 0 && a.win_gather) {
-    hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 4>), dim3(a.end_tile), dim3(256), pipe_lds_bytes(4), (hipStream_t)stream, a, NoMix());
-  } else if (a.end_tile > 0) {
-    hipLaunchKernelGGL((attn_bf16_kernel<4>), dim3(a.end_tile), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+  const bool grouped = a.win_gather && !win_long && rl.count[1] > 0;
+  if (grouped) {
+    // tiles of at most 128 tokens, gathered: the plan's grouped items -- those of more than 128
+    // rows (two or three tiles with one key set) on the 8-wavefront instance, the rest on the
+    // 4-wavefront one
+    if (int rc = fill_attn_args(p, win_rl, io, BM_LONG, WIN_TILES, &a, 0)) return rc;
+    if (a.end_tile > 0) {
+      const int n_split = std::min(a.end_tile, p->n_cus / 2);
+      a.split_from = a.end_tile - n_split;
+      hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 8>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a, NoMix());
+    }
+    if (int rc = fill_attn_args(p, win_rl, io, BM, WIN_TILES, &a, 1)) return rc;
+    if (a.end_tile > 0)
+      hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 4>), dim3(a.end_tile), dim3(256), pipe_lds_bytes(4), (hipStream_t)stream, a, NoMix());
+  } else {
+    if (int rc = fill_attn_args(p, win_rl, io, win_long ? BM_LONG : BM, WIN_TILES, &a)) return rc;
+    if (a.end_tile > 0 && win_long) {
+      const int n_split = std::min(a.end_tile, p->n_cus / 2);
+      a.split_from = a.end_tile - n_split;
+      hipLaunchKernelGGL((attn_bf16_pipe_kernel<true, 8>), dim3(a.end_tile + n_split), dim3(512), pipe_lds_bytes(8), (hipStream_t)stream, a, NoMix());
+    } else if (a.end_tile > 0) {
+      hipLaunchKernelGGL((attn_bf16_kernel<4>), dim3(a.end_tile), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+    }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(VORTA_EHIP, "launch of attn_bf16 kernels: %s", hipGetErrorString(e));

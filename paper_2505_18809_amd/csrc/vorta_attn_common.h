@@ -38,6 +38,14 @@ struct AttnArgs {
   int max_runs;
   int N, Nc, L, n_text;
   int n_tiles, tile_tokens;
+  // Route 1, gathered form, tiles of at most 128 tokens: window tiles whose key sets are identical
+  // (under the clamped centre rule the first floor(w/2) + 1 tiles of every axis end, under the
+  // block rule all tiles of a block) are computed together, up to three tiles and 256 rows per
+  // work item -- one key stream serves them all.  win_items[i] = {tile, tile, tile, count};
+  // a launch covers entries [win_first, win_first + win_count) for every window head.
+  // Null: one item per (tile, q-block), by arithmetic.
+  const int* win_items;
+  int win_first, win_count;
   // The last work items of a launch leave most CUs idle while a few finish them.  Items with
   // index >= split_from are therefore issued as two items of BM / 2 rows each (grid index
   // split_from + 2 j + h -> rows [h BM / 2, (h + 1) BM / 2) of item split_from + j); a workgroup
@@ -69,7 +77,15 @@ struct WorkItem {
   long row_stride;             // elements
   int head;                    // head id (dense segment only)
   int seg;                     // 0 dense, 1 core-set, 2 window
-  int row0, n_rows;            // query rows [row0, row0 + n_rows)
+  int row0, n_rows;            // query rows: n_rows of them; row i is row(i) below
+  // an item made of several tiles: its rows are up to three ranges of tile-order rows, range 0
+  // from row0, the others from rb1, rb2; rc0, rc1 = rows before range 1, range 2; first = the
+  // workgroup's first row within the item.  Single range: rc0 = INT_MAX, first = 0.
+  int rb1, rb2, rc0, rc1, first;
+  __device__ __forceinline__ int row(int i) const {
+    const int r = first + i;
+    return r < rc0 ? row0 + r : r < rc1 ? rb1 + (r - rc0) : rb2 + (r - rc1);
+  }
   int n_runs;
   const int* runs;             // null: the single run {0, single_len}
   int single_len;
@@ -81,6 +97,8 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
   w.runs = nullptr;
   w.n_runs = 1;
   w.head = 0;
+  w.rb1 = w.rb2 = w.first = 0;
+  w.rc0 = w.rc1 = 0x7fffffff;
   int half = -1;
   if (item >= a.split_from) {
     half = (item - a.split_from) & 1;
@@ -113,6 +131,36 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int item) {
     w.row0 = qb * BM;
     w.n_rows = min(BM, a.Nc - w.row0);
     w.single_len = a.Nc;
+  } else if (a.win_items) {
+    item -= a.end_core;
+    const int slot = item / a.win_count, i = item - slot * a.win_count;
+    const int* it = a.win_items + 4 * (a.win_first + i);
+    const int t0 = it[0], count = it[3];
+    w.seg = 2;
+    w.q_off = w.kv_off = w.o_off = a.win_heads[slot] * a.head_stride0;    // gathered form only
+    w.row_stride = a.row_stride0;
+    w.row0 = a.tile_row0[t0];
+    w.n_rows = a.tile_row0[t0 + 1] - w.row0;
+    if (count > 1) {
+      const int t1 = it[1];
+      w.rb1 = a.tile_row0[t1];
+      w.rc0 = w.n_rows;
+      w.n_rows += a.tile_row0[t1 + 1] - w.rb1;
+    }
+    if (count > 2) {
+      const int t2 = it[2];
+      w.rb2 = a.tile_row0[t2];
+      w.rc1 = w.n_rows;
+      w.n_rows += a.tile_row0[t2 + 1] - w.rb2;
+    }
+    w.runs = a.runs + (long)t0 * a.max_runs * 2;      // the same for every tile of the item
+    w.n_runs = a.n_runs[t0];
+    w.single_len = 0;
+    if (half >= 0) {
+      w.first = half * (BM / 2);
+      w.n_rows = min(BM / 2, w.n_rows - w.first);
+    }
+    return w;
   } else {
     item -= a.end_core;
     const int per_head = a.n_tiles * a.qb_tile;
@@ -151,8 +199,10 @@ __device__ __forceinline__ int xcd_item(int block, int n, bool chunked) {
 enum WindowPart { WIN_NONE = 0, WIN_TEXT = 1, WIN_TILES = 2, WIN_ALL = 3 };
 
 // Fills AttnArgs for a launch over the heads of rl with BM-row work items; win_part selects
-// which items of the window heads it carries.
-int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, int win_part, AttnArgs* a);
+// which items of the window heads it carries.  win_list: -1 = one item per (tile, q-block);
+// 0 / 1 = the plan's grouped items of more than 128 rows / of at most 128 rows.
+int fill_attn_args(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, int BM, int win_part, AttnArgs* a,
+                   int win_list = -1);
 
 int launch_attention_bf16(vorta_plan* p, const RouteLists& rl, const vorta_attn_io* io, void* stream,
                           const MixArgs* mix = nullptr, bool win_text = true);

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnArgs a) {
   if (w.n_rows <= 0) return;       // q-block past the end of a clipped tile
   const int t = threadIdx.x;
   const int quarter = t & 3, r_local = t >> 2;
-  const long my_row = w.row0 + min(r_local, w.n_rows - 1);
+  const long my_row = w.row(min(r_local, w.n_rows - 1));
 
   float4 q[CH];
   double o[CH][4];

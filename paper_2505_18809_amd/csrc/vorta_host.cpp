@@ -1,10 +1,12 @@
 // Host side of libvorta: plan construction, integer index tables, route bookkeeping.
 // Nothing in this file touches the GPU.
 #include <algorithm>
+#include <array>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <new>
 
 #include "vorta_internal.h"
@@ -229,6 +231,42 @@ int vorta_plan_create(const vorta_layer_desc* desc, vorta_plan** out) {
     std::copy(run_lists[t].begin(), run_lists[t].end(), p->runs.begin() + (size_t)t * p->max_runs * 2);
   }
 
+  // Window work items.  Query tiles whose run lists are identical see the same keys (under the
+  // clamped centre rule the border tile and its inner neighbour on every axis, under the block
+  // rule all tiles of a block): they are computed together, greedily up to three tiles and 256
+  // rows per item, so that one pass over the key stream serves them all.
+  if (p->tile_tokens <= 128) {
+    std::map<std::vector<int32_t>, std::vector<int>> same_keys;
+    for (int t = 0; t < p->n_tiles; ++t) same_keys[run_lists[t]].push_back(t);
+    std::vector<std::array<int32_t, 4>> big, small;
+    auto flush = [&](std::array<int32_t, 4>& item, int rows) {
+      if (item[3] == 0) return;
+      (rows > 128 ? big : small).push_back(item);
+      item = {0, 0, 0, 0};
+    };
+    for (auto& group : same_keys) {
+      std::array<int32_t, 4> item = {0, 0, 0, 0};
+      int rows = 0;
+      for (int t : group.second) {                       // ascending tile ids
+        const int n = p->tile_row0[t + 1] - p->tile_row0[t];
+        if (item[3] == 3 || rows + n > 256) {
+          flush(item, rows);
+          rows = 0;
+        }
+        item[item[3]++] = t;
+        rows += n;
+      }
+      flush(item, rows);
+    }
+    auto by_first_tile = [](const std::array<int32_t, 4>& a, const std::array<int32_t, 4>& b) { return a[0] < b[0]; };
+    std::sort(big.begin(), big.end(), by_first_tile);    // neighbours in the list are neighbours on the grid
+    std::sort(small.begin(), small.end(), by_first_tile);
+    p->n_win_big = (int)big.size();
+    p->n_win_small = (int)small.size();
+    for (auto* list : {&big, &small})
+      for (auto& item : *list) p->win_items.insert(p->win_items.end(), item.begin(), item.end());
+  }
+
   // BCS slot layout: a (border-clipped) bucket of B' tokens keeps B' - k of them,
   // k = min(B' - 1, floor(B' (den - num) / den)).
   p->slot_base.resize((size_t)p->n_buckets + 1);
@@ -325,6 +363,15 @@ int vorta_window_runs(const vorta_plan* p, int32_t* runs, int32_t* n_runs) {
   if (!p || !runs || !n_runs) return fail(VORTA_EINVAL, "null argument");
   std::copy(p->runs.begin(), p->runs.end(), runs);
   std::copy(p->n_runs.begin(), p->n_runs.end(), n_runs);
+  return VORTA_OK;
+}
+
+int vorta_window_items(const vorta_plan* p, int32_t* items, int32_t counts[2]) {
+  clear_error();
+  if (!p || !counts) return fail(VORTA_EINVAL, "null argument");
+  counts[0] = p->n_win_big;
+  counts[1] = p->n_win_small;
+  if (items) std::copy(p->win_items.begin(), p->win_items.end(), items);
   return VORTA_OK;
 }
 

@@ -26,6 +26,11 @@ struct vorta_plan {
   std::vector<int32_t> runs;     // [n_tiles][max_runs][2]
   std::vector<int32_t> n_runs;   // [n_tiles]
   std::vector<int32_t> slot_base;  // [n_buckets + 1]
+  // window work items (tiles of at most 128 tokens): tiles with identical key sets grouped, up to
+  // three tiles and 256 rows per item; {tile, tile, tile, count} each, the n_win_big items of more
+  // than 128 rows first, then the n_win_small others.  Empty when a tile holds more than 128 tokens.
+  std::vector<int32_t> win_items;
+  int n_win_big = 0, n_win_small = 0;
   // rotary embedding: (cos, sin) of position * rate for every position of every axis,
   // [F][pairs_F] then [H][pairs_H] then [W][pairs_W]; empty without rope_dims
   bool rope = false;
@@ -43,6 +48,7 @@ struct vorta_plan {
   int32_t* d_tok_of = nullptr;   // [N]
   int32_t* d_tile_row0 = nullptr;   // [n_tiles + 1]
   float* d_rope_cs = nullptr;
+  int32_t* d_win_items = nullptr;
 };
 
 namespace vorta {

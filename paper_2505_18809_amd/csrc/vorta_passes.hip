@@ -40,6 +40,8 @@ static void release_device_tables(vorta_plan* p) {
   }
   if (p->d_rope_cs) (void)hipFree(p->d_rope_cs);
   p->d_rope_cs = nullptr;
+  if (p->d_win_items) (void)hipFree(p->d_win_items);
+  p->d_win_items = nullptr;
 }
 // vorta_plan_destroy lives with the host code; it frees the device tables through this hook
 static const bool release_hook_set = (g_release_device_tables = release_device_tables, true);
@@ -57,6 +59,8 @@ static int upload_device_tables(vorta_plan* p, int dev) {
   if (int rc = upload_table(tok_of, &p->d_tok_of)) return rc;
   if (p->rope)
     if (int rc = upload_table(p->rope_cs, &p->d_rope_cs)) return rc;
+  if (!p->win_items.empty())
+    if (int rc = upload_table(p->win_items, &p->d_win_items)) return rc;
   int cus = 0;
   VORTA_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   if (cus > 0) p->n_cus = cus;

@@ -172,6 +172,39 @@ def test_tiles_and_buckets_larger_than_the_grid_are_clipped_to_it(tile, bucket):
         assert row0[t] <= perm[i] < row0[t + 1]
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("grid,tile,window", [((21, 45, 80), (3, 5, 8), (3, 3, 3)), ((21, 30, 52), (3, 6, 4), (3, 3, 3)),
+                                              ((5, 7, 6), (2, 3, 4), (3, 1, 5)), ((4, 8, 8), (1, 1, 1), (3, 3, 3)),
+                                              ((12, 16, 16), (4, 4, 4), (3, 3, 3)), ((9, 11, 14), (4, 6, 8), (3, 3, 3))])
+def test_window_items_group_tiles_with_identical_key_sets(grid, tile, window, mode):
+    """Every tile in exactly one item; the tiles of an item have the same run list (so one key
+    stream serves them), at most three tiles and 256 rows; items of more than 128 rows come first."""
+    plan = vorta.vorta_plan_create(grid, 1, 128, "bf16", tile, window, n_text=3, center_mode=mode)
+    big, small = vorta.vorta_window_items(plan)
+    if plan.tile_tokens > 128:
+        assert len(big) == 0 and len(small) == 0
+        return
+    runs, n_runs = vorta.vorta_window_runs(plan)
+    rows_of = np.diff(vorta.vorta_tile_row0(plan))
+    seen = []
+    for items, is_big in ((big, True), (small, False)):
+        assert (np.diff(items[:, 0]) > 0).all()
+        for it in items:
+            tiles = list(it[:it[3]])
+            assert 1 <= it[3] <= 3 and tiles == sorted(tiles)
+            rows = int(rows_of[tiles].sum())
+            assert rows <= 256 and (rows > 128) == is_big
+            for t in tiles[1:]:
+                assert n_runs[t] == n_runs[tiles[0]] and (runs[t, :n_runs[t]] == runs[tiles[0], :n_runs[t]]).all()
+            seen += tiles
+    assert sorted(seen) == list(range(plan.n_tiles))
+    if mode == 0 and grid == (21, 45, 80):
+        # clamped 3x3x3 window on 7x9x10 tiles: only the 3x5x6 interior tiles have a key set of their own
+        assert len(small) == 90 and len(big) == 270
+    if mode == 1 and window == (3, 3, 3) and min(plan.tiles) >= 3:
+        assert len(big) == 0 and len(small) == plan.n_tiles      # identity centres: all key sets differ
+
+
 def test_window_covering_the_grid_is_one_run():
     cfg = get_config("tiny")
     plan = vorta.plan_for(cfg)
