@@ -116,3 +116,26 @@ def test_layer_with_rope_equals_its_staged_calls():
     vorta.vorta_scatter_back(plan, routes, None, o_c, assign, staged)
     torch.cuda.synchronize()
     assert torch.equal(out, staged)
+
+
+def test_wan480p_sized_layer_with_rope_hard_routed_and_mixed():
+    """The 480p grid (32,760 tokens, 72-token tiles, grouped window items, fused selection +
+    pooling) with a Wan-style rotary split: three heads, one per route, then the same three heads
+    under Eq. 5 -- sampled rows of every head against the oracle."""
+    base = get_config("wan480p")
+    cfg = LayerConfig("wan480p_rope", base.grid, 3, 128, "bf16", base.tile, base.window, seed=83,
+                      fixed_routes=(0, 1, 2), rope_dims=WAN_ROPE)
+    L = cfg.n_video
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([rng.choice(L, 384, replace=False), np.arange(0, 72), np.arange(L - 3, L)]))
+    say("wan480p-sized layer with rope: hard routing")
+    plan, out = check_layer(cfg, cfg.fixed_routes, rows=rows)
+    q, k, v = make_qkv(cfg, DEV)
+    alpha = np.array([[0.5, 0.3, 0.2], [0.1, 0.6, 0.3], [0.3, 0.3, 0.4]], dtype=np.float32)
+    say("wan480p-sized layer with rope: soft mixture")
+    mixed = vorta.vorta_soft_mixture_layer(plan, q, k, v, alpha)
+    torch.cuda.synchronize()
+    want = vo.soft_mixture_layer(f64(q), f64(k), f64(v), alpha.astype(np.float64), spec_of(cfg), rows)
+    err = np.abs(f64(mixed[:, torch.as_tensor(rows, device=DEV)]) - want).max(axis=(1, 2))
+    say(f"  soft mixture max-abs per head {np.array2string(err, precision=4)}")
+    assert err.max() <= TOL["bf16"]
