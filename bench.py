@@ -113,19 +113,29 @@ def mfma_probe(torch, dev):
         "constant_1.0": torch.ones(16 * 64 * 8),
         "normal": torch.randn(16 * 64 * 8, generator=gen),
     }
-    for name, vals in kinds.items():
-        ops = vals.to(torch.bfloat16).to(dev)
+    def rate(ops, shape=32, vector_ops=0):
         iters, wgs = 4000, 256 * 4
-        probe.mfma_probe_rate(ops, 200, wgs)            # warm-up
+        probe.mfma_probe_rate(ops, 200, wgs, shape, vector_ops)            # warm-up
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        flops, _, clocks = probe.mfma_probe_rate(ops, iters, wgs)
+        flops, _, clocks = probe.mfma_probe_rate(ops, iters, wgs, shape, vector_ops)
         e1.record()
         torch.cuda.synchronize()
         c = clocks.cpu().tolist()
-        out[name] = {"TFLOP/s": flops / (e0.elapsed_time(e1) * 1e-3) / 1e12,
-                     "shader_clock_MHz": c[0] / max(c[1], 1) * 100.0}
+        return {"TFLOP/s": flops / (e0.elapsed_time(e1) * 1e-3) / 1e12,
+                "shader_clock_MHz": c[0] / max(c[1], 1) * 100.0}
+
+    for name, vals in kinds.items():
+        out[name] = rate(vals.to(torch.bfloat16).to(dev))
+    # the other bf16 shape on the same random operands (what the power limit leaves of it), and, on
+    # zero operands (no power limit), what 2, 3 and 4 vector instructions per 16 cycles of
+    # matrix-pipe time leave of either shape's rate: the vector issue port's share of a matrix instruction
+    out["normal_16x16x32"] = rate(kinds["normal"].to(torch.bfloat16).to(dev), shape=16)
+    zeros = kinds["zeros"].to(torch.bfloat16).to(dev)
+    out["zeros_with_vector_ops_TFLOPs"] = {
+        f"{name}": {str(kv): round(rate(zeros, shape, kv)["TFLOP/s"], 1) for kv in (0, 2, 3, 4)}
+        for name, shape in (("32x32x16", 32), ("16x16x32", 16))}
     return out
 
 
