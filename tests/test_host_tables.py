@@ -24,6 +24,21 @@ def test_library_exports_every_declared_symbol():
     assert lib.vorta_strerror(-2) == b"unsupported shape"
 
 
+def test_probe_library_loads_and_rejects_bad_arguments():
+    """The benchmark's matrix-rate probe is a library of its own; without a GPU only its
+    argument checks can run (they return before any launch)."""
+    from paper_2505_18809_amd import probe
+    lib = ctypes.CDLL(probe.PROBE_LIB_PATH)
+    fn = lib.mfma_probe_rate
+    fn.restype = ctypes.c_int
+    null, one = ctypes.c_void_p(0), ctypes.c_void_p(256)
+    assert fn(null, 1, 1, 32, 0, one, one, null) == -1          # no operands
+    assert fn(one, 0, 1, 32, 0, one, one, null) == -1           # no trips
+    assert fn(one, 1, 1, 8, 0, one, one, null) == -1            # unknown shape
+    assert fn(one, 1, 1, 16, 1, one, one, null) == -1           # unknown number of vector instructions
+    assert not hasattr(vorta.load_library(), "mfma_probe_rate")  # and it is not part of libvorta
+
+
 def test_struct_sizes_match_the_header():
     # 8 scalars + 3+3 ints + center_mode + 3 ints + 2 ints + float + 3 ints + float = 25 four-byte fields
     assert ctypes.sizeof(vorta.binding.vorta_layer_desc) == 25 * 4
