@@ -237,73 +237,68 @@ def main():
     attn_ms = stage_ms["attention_routed"]
     peak = MFMA_PEAK_TFLOPS[cfg.dtype]
 
-    # dominant kernel alone: the dense and core-set heads of this layer form one launch of the
-    # pipelined kernel (the window heads are a second, much shorter launch).  The same item
-    # list is reproduced with a plan that holds only those heads, and timed with events.
-    dom = {"kernel": "attn_f32_kernel", "ms": attn_ms, "flops": flops}
-    if cfg.dtype == "bf16" and counts[0] + counts[2] > 0:
-        sel = np.nonzero(routes != 1)[0]
+    # Attention of a subset of the heads alone: a plan that holds only those heads reproduces their
+    # items of the layer's launches exactly; timed with events on the stream of the launches.
+    def heads_alone(mask, zero=False):
+        sel = np.nonzero(mask)[0]
         sub_routes = np.ascontiguousarray(routes[sel])
         sub_plan = vorta.plan_for(cfg, layout=args.layout, heads=len(sel))
         idx = torch.as_tensor(sel, device=dev)
         hd = 0 if args.layout == 1 else 1
         sq, sk, sv = (t.index_select(hd, idx).contiguous() for t in (q, k, v))
         so = torch.empty_like(sq)
-        sws = torch.empty(vorta.vorta_workspace_bytes(sub_plan, sub_routes), dtype=torch.uint8, device=dev)
-        vorta.vorta_routed_attention_layer(sub_plan, sq, sk, sv, sub_routes, out=so, workspace=sws)   # fills the pooled buffers
-        soff = vorta.vorta_workspace_layout(sub_plan, sub_routes)
-        def sbuf(i):
-            return sws[soff[i]: soff[i] + n_lr * plan.n_core_tokens * row].view(q.dtype).view(n_lr, plan.n_core_tokens, cfg.head_dim)
         kw = dict(q=sq, k=sk, v=sv, out=so)
-        if n_lr:
-            kw.update(q_c=sbuf(4), k_c=sbuf(5), v_c=sbuf(6), o_c=sbuf(7))
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
-        e0.record()
-        for _ in range(args.steps):
+        n_core = int((sub_routes == 2).sum())
+        pooled = ()
+        if n_core:
+            sws = torch.empty(vorta.vorta_workspace_bytes(sub_plan, sub_routes), dtype=torch.uint8, device=dev)
+            vorta.vorta_routed_attention_layer(sub_plan, sq, sk, sv, sub_routes, out=so, workspace=sws)   # fills the pooled buffers
+            soff = vorta.vorta_workspace_layout(sub_plan, sub_routes)
+            def sbuf(i):
+                return sws[soff[i]: soff[i] + n_core * plan.n_core_tokens * row].view(q.dtype).view(n_core, plan.n_core_tokens, cfg.head_dim)
+            pooled = (sbuf(4), sbuf(5), sbuf(6))
+            kw.update(q_c=pooled[0], k_c=pooled[1], v_c=pooled[2], o_c=sbuf(7))
+
+        def timed(n):
             vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
-        e1.record()
-        torch.cuda.synchronize()
-        dom = {"kernel": "attn_bf16_pipe_kernel<false, 8>", "ms": e0.elapsed_time(e1) / args.steps,
-               "flops": per_route[0] + per_route[2]}
-        # The same launch on all-zero operands: the same instructions and cycle count, but no
-        # operand bit toggles, so the power limit does not hold the clock down.  A diagnostic
-        # of what the limit costs on real data, not a throughput claim.
-        # Off by default, so that a profile of the default command holds launches of one kind.
-        if args.zero_operands:
-            for t in (sq, sk, sv) + ((sbuf(4), sbuf(5), sbuf(6)) if n_lr else ()):
-                t.zero_()
-            vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            for _ in range(3):
+            for _ in range(n):
                 vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
             e1.record()
             torch.cuda.synchronize()
-            dom["zero_ms"] = e0.elapsed_time(e1) / 3
-        del sq, sk, sv, so, sws
-    # the window heads alone, the same way (their tiles are the attention call's second launch;
-    # their text rows, if the layer has text tokens, ride in a short launch of the pipelined kernel)
+            return e0.elapsed_time(e1) / n
+
+        res = {"ms": timed(args.steps)}
+        # The same launch on all-zero operands: the same instructions and cycle count, but no
+        # operand bit toggles, so the power limit does not hold the clock down.  A diagnostic
+        # of what the limit costs on real data, not a throughput claim.
+        if zero:
+            for t in (sq, sk, sv) + pooled:
+                t.zero_()
+            res["zero_ms"] = timed(3)
+        return res
+
+    # dominant kernel alone: the dense and core-set heads of this layer form one launch of the
+    # pipelined kernel (the window heads are the launches after it)
+    dom = {"kernel": "attn_f32_kernel", "ms": attn_ms, "flops": flops}
     win_ms = None
-    if cfg.dtype == "bf16" and counts[1] > 0:
-        sel = np.nonzero(routes == 1)[0]
-        sub_routes = np.ascontiguousarray(routes[sel])
-        sub_plan = vorta.plan_for(cfg, layout=args.layout, heads=len(sel))
-        idx = torch.as_tensor(sel, device=dev)
-        hd = 0 if args.layout == 1 else 1
-        sq, sk, sv = (t.index_select(hd, idx).contiguous() for t in (q, k, v))
-        so = torch.empty_like(sq)
-        kw = dict(q=sq, k=sk, v=sv, out=so)
-        vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
-            vorta.vorta_attention_routed(sub_plan, sub_routes, **kw)
-        e1.record()
-        torch.cuda.synchronize()
-        win_ms = e0.elapsed_time(e1) / args.steps
-        del sq, sk, sv, so
+    route_alone = {}
+    if cfg.dtype == "bf16":
+        if counts[0] + counts[2] > 0:
+            # (zero operands: off by default, so that a profile of the default command holds launches of one kind)
+            dom = {"kernel": "attn_bf16_pipe_kernel<false, 8>", "flops": per_route[0] + per_route[2],
+                   **heads_alone(routes != 1, zero=args.zero_operands)}
+        # the window heads alone (their tiles are the attention call's later launches; their text
+        # rows, if the layer has text tokens, ride in a short launch of the pipelined kernel)
+        if counts[1] > 0:
+            win_ms = heads_alone(routes == 1)["ms"]
+        # and every route alone
+        for r, name in enumerate(("full", "window", "core-set")):
+            if counts[r] > 0:
+                r_ms = win_ms if r == 1 else heads_alone(routes == r)["ms"]
+                route_alone[name] = {"heads": counts[r], "ms": r_ms, "TFLOP/s": per_route[r] / (r_ms * 1e-3) / 1e12}
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
     traffic = profiled_traffic(dom["kernel"], args.workload, args.layout)
     result = {
@@ -339,6 +334,7 @@ def main():
             "dense+core-set": {"ms": dom["ms"], "TFLOP/s": dom["flops"] / (dom["ms"] * 1e-3) / 1e12},
             "window": ({"ms": win_ms, "TFLOP/s": per_route[1] / (win_ms * 1e-3) / 1e12} if win_ms else None),
         },
+        "routes_alone": route_alone,
         "memory_passes_GBps": {n: pass_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in pass_bytes if stage_ms.get(n, 0) > 0},
     }
     if cfg.dtype == "bf16":
