@@ -149,6 +149,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--zero-operands", action="store_true",
                     help="also time the dominant kernel's launch on all-zero Q/K/V (what the power limit costs on real data)")
+    ap.add_argument("--routes-alone", action="store_true",
+                    help="also time the heads of each route alone (per-route TFLOP/s); off by default like --zero-operands")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -294,9 +296,10 @@ def main():
         # rows, if the layer has text tokens, ride in a short launch of the pipelined kernel)
         if counts[1] > 0:
             win_ms = heads_alone(routes == 1)["ms"]
-        # and every route alone
+        # and, on request, every route alone (launches of the dominant kernel on other head sets:
+        # off by default for the same reason as the zero operands)
         for r, name in enumerate(("full", "window", "core-set")):
-            if counts[r] > 0:
+            if args.routes_alone and counts[r] > 0:
                 r_ms = win_ms if r == 1 else heads_alone(routes == r)["ms"]
                 route_alone[name] = {"heads": counts[r], "ms": r_ms, "TFLOP/s": per_route[r] / (r_ms * 1e-3) / 1e12}
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
@@ -334,7 +337,7 @@ def main():
             "dense+core-set": {"ms": dom["ms"], "TFLOP/s": dom["flops"] / (dom["ms"] * 1e-3) / 1e12},
             "window": ({"ms": win_ms, "TFLOP/s": per_route[1] / (win_ms * 1e-3) / 1e12} if win_ms else None),
         },
-        "routes_alone": route_alone,
+        "routes_alone": route_alone or None,
         "memory_passes_GBps": {n: pass_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in pass_bytes if stage_ms.get(n, 0) > 0},
     }
     if cfg.dtype == "bf16":
